@@ -1,0 +1,347 @@
+/*
+ * moe_oracle.c - plain CPU oracle for the sparse MoE feed-forward layer.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, obviously-correct statement
+ * of what the layer computes, written from the paper's definitions (CoSMoEs,
+ * arXiv 2503.00245).  Only the test-suite, the smoke check and the bench's CPU
+ * baseline leg may call it; the GPU library never does, and the two share no
+ * source, header, table or helper.
+ *
+ * All arithmetic is fp64.  Stored inputs (fp32, or bf16 bit patterns) are
+ * widened exactly; nothing is rounded on the way.  Loops follow the formulas
+ * term by term; the only parallelism is OpenMP over independent tokens or
+ * independent output rows, which does not change any sum's order.
+ *
+ * What each function follows:
+ *   oracle_route        Sec. 2.3: logits R (B,T,E) with B folded into T; Eq. 2
+ *                       W = softmax(tau R) at tau = 1; Eq. 3 S = top_k(W, K).
+ *                       Gate renormalisation over the k chosen, descending order
+ *                       and lowest-index tie-break are this build's stated
+ *                       conventions (the paper defers to "standard approaches").
+ *   oracle_permute      dispatch of Fig. 2 (token-choice routing) as a textbook
+ *                       stable counting sort of (token, slot) pairs by expert.
+ *   oracle_expert_ffn   Sec. 3.1 (Llama-style block => bias-free SwiGLU expert);
+ *                       Sec. 2.2 Eq. 1 for weight-decomposed matrices M = L R.
+ *   oracle_combine      Sec. 1 / Sec. 2.1: the gate weights each expert's output.
+ *   oracle_forward      the whole layer, token by token, WITHOUT permuting:
+ *                       y[t] = sum_j g[t,j] FFN_{S[t,j]}(x[t]).
+ *   oracle_stack_forward  x_{l+1} = x_l + layer_l(x_l) (benchmark construct, not
+ *                       in the paper: no attention, no normalisation).
+ *   oracle_expert_replacements  Sec. 2.3 Eq. 4 (H_e, H) and the floor(H/2) of Eq. 5.
+ *
+ * Parity pins (tests/test_oracle_*.py): closed forms, library routines on
+ * special cases, brute force on tiny inputs and the worked example of Fig. 5.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#else
+static int omp_in_parallel(void) { return 0; }
+#endif
+
+enum { DT_F32 = 0, DT_BF16 = 1 };
+enum { FLAG_SHARED_BASE = 1, FLAG_RESIDUAL = 2 };
+
+/* Own argument block (deliberately not the GPU library's struct). */
+typedef struct oracle_layer {
+    int32_t d, F, E, k, r, dtype, flags;
+    const float* router_w; /* [E,d] */
+    const float* router_b; /* [E] or NULL */
+    const void *w_gate, *w_up, *w_down;    /* [Eb,F,d] [Eb,F,d] [Eb,d,F] or NULL */
+    const void *rg, *ru, *rd, *lg, *lu, *ld; /* Eq. 1 factors or NULL */
+} oracle_layer;
+
+static double elem(const void* p, size_t i, int dtype) {
+    if (dtype == DT_F32) return (double)((const float*)p)[i];
+    uint32_t bits = ((uint32_t)((const uint16_t*)p)[i]) << 16;
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return (double)f;
+}
+
+static void widen(const void* p, size_t off, size_t n, int dtype, double* out) {
+    for (size_t i = 0; i < n; ++i) out[i] = elem(p, off + i, dtype);
+}
+
+/* <row `row` of a [rows, n] matrix starting at element `base`, v>, summed in index order */
+static double row_dot(const void* m, size_t base, size_t row, int n, const double* v, int dtype) {
+    double acc = 0.0;
+    size_t off = base + row * (size_t)n;
+    if (dtype == DT_F32) {
+        const float* w = (const float*)m + off;
+        for (int i = 0; i < n; ++i) acc += (double)w[i] * v[i];
+    } else {
+        const uint16_t* w = (const uint16_t*)m + off;
+        for (int i = 0; i < n; ++i) {
+            uint32_t bits = ((uint32_t)w[i]) << 16;
+            float f;
+            memcpy(&f, &bits, sizeof f);
+            acc += (double)f * v[i];
+        }
+    }
+    return acc;
+}
+
+/* out[o] = sum_i M[o,i] v[i] for the n_out x n_in matrix at element offset base */
+static void matvec(const void* m, size_t base, int n_out, int n_in, const double* v, int dtype,
+                   double* out, int accumulate) {
+#pragma omp parallel for schedule(static) if (!omp_in_parallel() && n_out >= 256)
+    for (int o = 0; o < n_out; ++o) {
+        double s = row_dot(m, base, (size_t)o, n_in, v, dtype);
+        out[o] = accumulate ? out[o] + s : s;
+    }
+}
+
+/*
+ * One expert matrix applied to a vector: M_e v, where M_e (n_out x n_in) is
+ *   dense:            W[e]                               (r == 0)
+ *   decomposed:       L[e] (R[e] v)                       (Eq. 1)
+ *   shared base:      W[0] v + L[e] (R[e] v)
+ */
+static void expert_matvec(const oracle_layer* L, int e, const void* dense, const void* Rf,
+                          const void* Lf, int n_out, int n_in, const double* v, double* out,
+                          double* tmp_r) {
+    int have = 0;
+    if (dense) {
+        size_t eb = (L->flags & FLAG_SHARED_BASE) ? 0 : (size_t)e;
+        matvec(dense, eb * (size_t)n_out * n_in, n_out, n_in, v, L->dtype, out, 0);
+        have = 1;
+    }
+    if (L->r > 0) {
+        matvec(Rf, (size_t)e * L->r * n_in, L->r, n_in, v, L->dtype, tmp_r, 0);
+        matvec(Lf, (size_t)e * n_out * L->r, n_out, L->r, tmp_r, L->dtype, out, have);
+    }
+}
+
+static double silu(double z) { return z / (1.0 + exp(-z)); }
+
+/* FFN_e(v) = W_down,e ( silu(W_gate,e v) * (W_up,e v) );  scratch: 2F + r doubles */
+static void expert_ffn_vec(const oracle_layer* L, int e, const double* v, double* out,
+                           double* scratch) {
+    double* g = scratch;
+    double* u = scratch + L->F;
+    double* tr = scratch + 2 * (size_t)L->F;
+    expert_matvec(L, e, L->w_gate, L->rg, L->lg, L->F, L->d, v, g, tr);
+    expert_matvec(L, e, L->w_up, L->ru, L->lu, L->F, L->d, v, u, tr);
+    for (int f = 0; f < L->F; ++f) g[f] = silu(g[f]) * u[f];
+    expert_matvec(L, e, L->w_down, L->rd, L->ld, L->d, L->F, g, out, tr);
+}
+
+/* Router for one widened token: logits, softmax, top-k, renormalised gates. */
+static void route_token(int d, int E, int k, const double* xv, const float* rw, const float* rb,
+                        double* logits, double* probs, int32_t* idx, double* gate) {
+    double mx = -INFINITY;
+    for (int e = 0; e < E; ++e) {
+        double acc = 0.0;
+        for (int i = 0; i < d; ++i) acc += xv[i] * (double)rw[(size_t)e * d + i];
+        if (rb) acc += (double)rb[e];
+        logits[e] = acc;
+        if (acc > mx) mx = acc;
+    }
+    double den = 0.0;
+    for (int e = 0; e < E; ++e) {
+        probs[e] = exp(logits[e] - mx);
+        den += probs[e];
+    }
+    for (int e = 0; e < E; ++e) probs[e] /= den;
+    /* k rounds of selection: largest logit not yet taken, lowest index among equals */
+    double sel = 0.0;
+    for (int j = 0; j < k; ++j) {
+        int best = -1;
+        for (int e = 0; e < E; ++e) {
+            int taken = 0;
+            for (int q = 0; q < j; ++q) taken |= (idx[q] == e);
+            if (taken) continue;
+            if (best < 0 || logits[e] > logits[best]) best = e;
+        }
+        idx[j] = best;
+        sel += probs[best];
+    }
+    for (int j = 0; j < k; ++j) gate[j] = probs[idx[j]] / sel;
+}
+
+int oracle_route(int T, int d, int E, int k, int dtype, const void* x, const float* rw,
+                 const float* rb, int32_t* topk_idx, double* topk_gate, double* probs_out,
+                 double* logits_out) {
+    if (T < 0 || d < 1 || E < 1 || k < 1 || k > E) return -1;
+#pragma omp parallel for schedule(static) if (T >= 8)
+    for (int t = 0; t < T; ++t) {
+        double* xv = (double*)malloc(sizeof(double) * ((size_t)d + 2 * (size_t)E));
+        double* lg = xv + d;
+        double* pr = lg + E;
+        widen(x, (size_t)t * d, (size_t)d, dtype, xv);
+        route_token(d, E, k, xv, rw, rb, lg, pr, topk_idx + (size_t)t * k,
+                    topk_gate + (size_t)t * k);
+        if (probs_out) memcpy(probs_out + (size_t)t * E, pr, sizeof(double) * E);
+        if (logits_out) memcpy(logits_out + (size_t)t * E, lg, sizeof(double) * E);
+        free(xv);
+    }
+    return 0;
+}
+
+/* Stable counting sort of pairs p = 0..P-1 by key topk_idx[p] in [0,E). */
+int oracle_permute(int P, int E, const int32_t* topk_idx, int32_t* expert_offsets, int32_t* perm,
+                   int32_t* inv_perm) {
+    if (P < 0 || E < 1) return -1;
+    for (int e = 0; e <= E; ++e) expert_offsets[e] = 0;
+    for (int p = 0; p < P; ++p) {
+        if (topk_idx[p] < 0 || topk_idx[p] >= E) return -1;
+        expert_offsets[topk_idx[p] + 1] += 1;
+    }
+    for (int e = 0; e < E; ++e) expert_offsets[e + 1] += expert_offsets[e];
+    int32_t* next = (int32_t*)malloc(sizeof(int32_t) * (size_t)E);
+    for (int e = 0; e < E; ++e) next[e] = expert_offsets[e];
+    for (int p = 0; p < P; ++p) {
+        int32_t s = next[topk_idx[p]]++;
+        perm[s] = p;
+        inv_perm[p] = s;
+    }
+    free(next);
+    return 0;
+}
+
+/* y_perm[s,:] = FFN_e(x_perm[s,:]) for s in group e; x_perm stored in L->dtype. */
+int oracle_expert_ffn(const oracle_layer* L, int P, const void* x_perm,
+                      const int32_t* expert_offsets, double* y_perm) {
+    if (expert_offsets[0] != 0 || expert_offsets[L->E] != P) return -1;
+    int32_t* row_expert = (int32_t*)malloc(sizeof(int32_t) * (size_t)(P > 0 ? P : 1));
+    for (int e = 0; e < L->E; ++e)
+        for (int s = expert_offsets[e]; s < expert_offsets[e + 1]; ++s) row_expert[s] = e;
+#pragma omp parallel for schedule(dynamic, 1) if (P >= 8)
+    for (int s = 0; s < P; ++s) {
+        size_t ns = (size_t)L->d + 2 * (size_t)L->F + (size_t)L->r;
+        double* v = (double*)malloc(sizeof(double) * ns);
+        widen(x_perm, (size_t)s * L->d, (size_t)L->d, L->dtype, v);
+        expert_ffn_vec(L, row_expert[s], v, y_perm + (size_t)s * L->d, v + L->d);
+        free(v);
+    }
+    free(row_expert);
+    return 0;
+}
+
+/* y[t,:] = sum_j gate[t,j] y_perm[inv_perm[t k + j],:] (+ residual[t,:]), j ascending */
+int oracle_combine(int T, int d, int k, int dtype, const double* y_perm, const int32_t* inv_perm,
+                   const double* topk_gate, const void* residual, double* y) {
+    for (int t = 0; t < T; ++t) {
+        for (int i = 0; i < d; ++i) {
+            double acc = 0.0;
+            for (int j = 0; j < k; ++j) {
+                size_t s = (size_t)inv_perm[(size_t)t * k + j];
+                acc += topk_gate[(size_t)t * k + j] * y_perm[s * d + i];
+            }
+            if (residual) acc += elem(residual, (size_t)t * d + i, dtype);
+            y[(size_t)t * d + i] = acc;
+        }
+    }
+    return 0;
+}
+
+/* The layer on fp64 activations xin [T,d]; optional routing outputs. */
+static int layer_forward_f64(const oracle_layer* L, int T, const double* xin, double* y,
+                             int32_t* idx_out, double* gate_out) {
+    if (T < 0 || L->k < 1 || L->k > L->E) return -1;
+    const int d = L->d, k = L->k, E = L->E;
+#pragma omp parallel for schedule(dynamic, 1) if (T >= 8)
+    for (int t = 0; t < T; ++t) {
+        size_t ns = 2 * (size_t)E + (size_t)k + (size_t)d + 2 * (size_t)L->F + (size_t)L->r;
+        double* buf = (double*)malloc(sizeof(double) * ns);
+        int32_t* idx = (int32_t*)malloc(sizeof(int32_t) * (size_t)k);
+        double* lg = buf;
+        double* pr = lg + E;
+        double* gate = pr + E;
+        double* out = gate + k;
+        double* scratch = out + d;
+        const double* xv = xin + (size_t)t * d;
+        route_token(d, E, k, xv, L->router_w, L->router_b, lg, pr, idx, gate);
+        double* yt = y + (size_t)t * d;
+        for (int i = 0; i < d; ++i) yt[i] = 0.0;
+        for (int j = 0; j < k; ++j) {
+            expert_ffn_vec(L, idx[j], xv, out, scratch);
+            for (int i = 0; i < d; ++i) yt[i] += gate[j] * out[i];
+        }
+        if (L->flags & FLAG_RESIDUAL)
+            for (int i = 0; i < d; ++i) yt[i] += xv[i];
+        if (idx_out) memcpy(idx_out + (size_t)t * k, idx, sizeof(int32_t) * k);
+        if (gate_out) memcpy(gate_out + (size_t)t * k, gate, sizeof(double) * k);
+        free(idx);
+        free(buf);
+    }
+    return 0;
+}
+
+int oracle_forward(const oracle_layer* L, int T, const void* x, double* y, int32_t* idx_out,
+                   double* gate_out) {
+    size_t n = (size_t)(T > 0 ? T : 0) * L->d;
+    double* xin = (double*)malloc(sizeof(double) * (n ? n : 1));
+    widen(x, 0, n, L->dtype, xin);
+    int rc = layer_forward_f64(L, T, xin, y, idx_out, gate_out);
+    free(xin);
+    return rc;
+}
+
+/*
+ * Residual stack.  Each layer's FLAG_RESIDUAL is forced on.  xs_out, if given,
+ * receives the fp64 input of every layer and the final output: [(n_layers+1), T, d].
+ * trace_out, if given: [n_layers, T, k] selected experts.
+ */
+int oracle_stack_forward(const oracle_layer* layers, int n_layers, int T, const void* x, double* y,
+                         int32_t* trace_out, double* xs_out) {
+    if (n_layers < 1) return -1;
+    const int d = layers[0].d, k = layers[0].k;
+    size_t n = (size_t)(T > 0 ? T : 0) * d;
+    double* cur = (double*)malloc(sizeof(double) * (n ? n : 1));
+    double* nxt = (double*)malloc(sizeof(double) * (n ? n : 1));
+    widen(x, 0, n, layers[0].dtype, cur);
+    int rc = 0;
+    for (int l = 0; l < n_layers && rc == 0; ++l) {
+        oracle_layer L = layers[l];
+        L.flags |= FLAG_RESIDUAL;
+        if (xs_out) memcpy(xs_out + (size_t)l * n, cur, sizeof(double) * n);
+        rc = layer_forward_f64(&L, T, cur, nxt, trace_out ? trace_out + (size_t)l * T * k : NULL,
+                               NULL);
+        double* sw = cur;
+        cur = nxt;
+        nxt = sw;
+    }
+    memcpy(y, cur, sizeof(double) * n);
+    if (xs_out) memcpy(xs_out + (size_t)n_layers * n, cur, sizeof(double) * n);
+    free(cur);
+    free(nxt);
+    return rc;
+}
+
+/*
+ * Hard expert replacements of Sec. 2.3, Eq. 4: S is [B,T,K] selected experts.
+ * H_e = sum_b sum_{t<T-1} | [e in S[b,t+1]] - [e in S[b,t]] |,  H = sum_e H_e.
+ * Returns H; H_e written to He[E].  Eq. 5's numerator is floor(H/2).
+ */
+int64_t oracle_expert_replacements(int B, int T, int K, int E, const int32_t* S, int64_t* He) {
+    int64_t H = 0;
+    for (int e = 0; e < E; ++e) {
+        int64_t h = 0;
+        for (int b = 0; b < B; ++b) {
+            for (int t = 0; t + 1 < T; ++t) {
+                int a0 = 0, a1 = 0;
+                for (int j = 0; j < K; ++j) {
+                    a0 |= (S[((size_t)b * T + t) * K + j] == e);
+                    a1 |= (S[((size_t)b * T + t + 1) * K + j] == e);
+                }
+                h += (a1 - a0) < 0 ? (a0 - a1) : (a1 - a0);
+            }
+        }
+        if (He) He[e] = h;
+        H += h;
+    }
+    return H;
+}
+
+int oracle_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

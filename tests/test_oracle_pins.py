@@ -1,0 +1,425 @@
+"""Pins of the CPU oracle against things other than itself (CPU only).
+
+Each test fixes part of the oracle to a closed form, a library routine on a
+special case, an invariant, a brute force on tiny inputs, or a value the paper
+prints.  Together they are chosen so a dropped term, a wrong sign or index, or
+a transposed operand in oracle/moe_oracle.c fails at least one of them.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import scipy.special
+import torch
+
+import workloads as wl
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rand_layer(seed, d, F, E, dtype="f32", r=0, shared_base=False, bias=False):
+    cfg = wl.LayerConfig("t", d, F, E, 2, dtype, seed, rank=r, shared_base=shared_base,
+                         weight_std=0.2, router_std=0.3, wd_product_std=0.2)
+    w = wl.make_layer_weights(cfg, with_bias=False)
+    if bias:
+        w["router_b"] = wl.normal_tensor(seed, 99, (E,), 0.5, "f32")
+    return cfg, w
+
+
+def _f64(a):
+    """stored tensor (float32 or bf16 bits) -> float64 values"""
+    if a.dtype == np.uint16:
+        a = wl.bf16_bits_to_f32(a)
+    return a.astype(np.float64)
+
+
+def _swiglu_torch(x, wg, wu, wd):
+    """Textbook SwiGLU FFN with library ops, fp64."""
+    x, wg, wu, wd = (torch.from_numpy(np.ascontiguousarray(a)) for a in (x, wg, wu, wd))
+    h = torch.nn.functional.silu(x @ wg.T) * (x @ wu.T)
+    return (h @ wd.T).numpy()
+
+
+# ----------------------------------------------------------------- input generator
+
+def test_bf16_rounding_matches_library_conversion():
+    a = np.random.default_rng(0).standard_normal(100000).astype(np.float32) * 3
+    a[:4] = [0.0, -0.0, 1.0039062, 1.0117188]  # the last two are exact ties in bf16
+    bits = wl.f32_to_bf16_bits(a)
+    ref = torch.from_numpy(a).to(torch.bfloat16)
+    assert np.array_equal(bits.view(np.int16), ref.view(torch.int16).numpy())
+    assert np.array_equal(wl.bf16_bits_to_f32(bits), ref.float().numpy())
+
+
+def test_generator_is_seeded_and_has_stated_moments():
+    a = wl.normal_tensor(7, 3, (4, 100, 50), 0.02, "f32")
+    b = wl.normal_tensor(7, 3, (4, 100, 50), 0.02, "f32")
+    c = wl.normal_tensor(8, 3, (4, 100, 50), 0.02, "f32")
+    assert np.array_equal(a, b) and not np.array_equal(a, c)
+    assert abs(a.std() - 0.02) < 5e-4 and abs(a.mean()) < 5e-4
+    assert not np.array_equal(a[0], a[1])
+
+
+def test_zipf_target_shares():
+    s = wl.zipf_target_shares(8, 1.1)
+    assert abs(s.sum() - 1) < 1e-12 and np.all(np.diff(s) < 0)
+    assert abs(s[0] / s[1] - 2 ** 1.1) < 1e-12
+    assert s[0] < 0.5  # feasible with one slot per token per expert
+
+
+# ----------------------------------------------------------------- router (Eq. 2, Eq. 3)
+
+def test_zero_router_gives_uniform_probabilities(oracle):
+    x = wl.normal_tensor(1, 1, (5, 16), 1.0, "f32")
+    idx, gate, probs, logits = oracle.route(x, np.zeros((8, 16), np.float32), None, 3)
+    assert np.all(logits == 0.0)
+    assert np.all(probs == 1.0 / 8)
+    assert np.array_equal(idx, np.tile(np.arange(3, dtype=np.int32), (5, 1)))
+    assert np.allclose(gate, 1.0 / 3, rtol=0, atol=1e-16)
+
+
+def test_logits_match_library_matmul_and_bias(oracle):
+    _, w = _rand_layer(11, 24, 8, 5, bias=True)
+    x = wl.normal_tensor(11, 1, (7, 24), 1.0, "f32")
+    _, _, probs, logits = oracle.route(x, w["router_w"], w["router_b"], 2)
+    ref = x.astype(np.float64) @ w["router_w"].astype(np.float64).T + w["router_b"].astype(np.float64)
+    assert np.allclose(logits, ref, rtol=1e-13, atol=1e-13)
+    assert np.allclose(probs, scipy.special.softmax(ref, axis=1), rtol=1e-12, atol=0)
+
+
+def test_one_hot_token_reads_one_router_column(oracle):
+    _, w = _rand_layer(12, 10, 8, 6, bias=True)
+    for i in (0, 3, 9):
+        x = np.zeros((1, 10), np.float32)
+        x[0, i] = 1.0
+        _, _, probs, logits = oracle.route(x, w["router_w"], w["router_b"], 2)
+        col = w["router_w"][:, i].astype(np.float64) + w["router_b"].astype(np.float64)
+        assert np.array_equal(logits[0], col)
+        assert np.allclose(probs[0], scipy.special.softmax(col), rtol=1e-13)
+
+
+def test_bf16_tokens_are_widened_exactly(oracle):
+    _, w = _rand_layer(13, 32, 8, 4)
+    xb = wl.normal_tensor(13, 1, (6, 32), 1.0, "bf16")
+    a = oracle.route(xb, w["router_w"], None, 2)
+    b = oracle.route(wl.bf16_bits_to_f32(xb), w["router_w"], None, 2)
+    for u, v in zip(a, b):
+        assert np.array_equal(u, v)
+
+
+def test_softmax_shift_invariance_and_normalisation(oracle):
+    _, w = _rand_layer(14, 20, 8, 8, bias=True)
+    x = wl.normal_tensor(14, 1, (9, 20), 1.0, "f32")
+    b = np.round(w["router_b"] * 64) / np.float32(64)  # so that b + 4 is exact in fp32
+    i0, g0, p0, _ = oracle.route(x, w["router_w"], b, 2)
+    i1, g1, p1, _ = oracle.route(x, w["router_w"], b + np.float32(4.0), 2)
+    assert np.array_equal(i0, i1)
+    assert np.allclose(p0, p1, rtol=1e-12) and np.allclose(g0, g1, rtol=1e-12)
+    assert np.allclose(p0.sum(1), 1.0, rtol=0, atol=8 * 2.3e-16)
+
+
+def test_softmax_survives_large_logits(oracle):
+    # logits near +-900 overflow exp() unless the maximum is subtracted first
+    x = np.array([[900.0, 899.0, -900.0, 898.5]], np.float32)
+    idx, gate, probs, _ = oracle.route(x, np.eye(4, dtype=np.float32), None, 2)
+    assert np.all(np.isfinite(probs))
+    assert np.allclose(probs, scipy.special.softmax(x.astype(np.float64), axis=1), rtol=1e-13)
+    assert list(idx[0]) == [0, 1] and np.allclose(gate[0], scipy.special.softmax([900.0, 899.0]))
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 6])
+def test_topk_matches_full_sort_with_ties(oracle, k):
+    # logits quantised to a handful of values so equal logits are common; the
+    # router is the identity so the logits ARE the (exactly representable) inputs
+    rng = np.random.default_rng(100 + k)
+    E = 6
+    x = rng.integers(-2, 3, size=(200, E)).astype(np.float32) * 0.5
+    rw = np.eye(E, dtype=np.float32)
+    idx, gate, probs, logits = oracle.route(x, rw, None, k)
+    assert np.array_equal(logits, x.astype(np.float64))
+    for t in range(x.shape[0]):
+        order = sorted(range(E), key=lambda e: (-float(x[t, e]), e))[:k]
+        assert list(idx[t]) == order
+    # gates: selected probabilities renormalised == softmax over the k chosen logits
+    chosen = np.take_along_axis(x.astype(np.float64), idx.astype(np.int64), axis=1)
+    assert np.allclose(gate, scipy.special.softmax(chosen, axis=1), rtol=1e-12)
+    assert np.allclose(gate.sum(1), 1.0, rtol=0, atol=4.5e-16)
+    if k == 1:
+        assert np.all(gate == 1.0)
+    if k == E:
+        assert np.allclose(gate, np.take_along_axis(probs, idx.astype(np.int64), 1), rtol=1e-12)
+
+
+def test_all_equal_logits_pick_lowest_indices(oracle):
+    x = np.ones((3, 4), np.float32)
+    rw = np.tile(np.array([[0.5, -0.25, 0.125, 1.0]], np.float32), (7, 1))  # 7 identical experts
+    idx, gate, _, _ = oracle.route(x, rw, None, 4)
+    assert np.array_equal(idx, np.tile(np.arange(4, dtype=np.int32), (3, 1)))
+    assert np.all(gate == 0.25)
+
+
+def test_route_rejects_bad_k(oracle):
+    x = np.zeros((1, 4), np.float32)
+    rw = np.zeros((3, 4), np.float32)
+    for k in (0, 4):
+        with pytest.raises(ValueError):
+            oracle.route(x, rw, None, k)
+
+
+# ----------------------------------------------------------------- dispatch
+
+@pytest.mark.parametrize("P,E", [(0, 3), (1, 1), (37, 4), (1000, 8), (513, 64)])
+def test_permute_is_the_stable_sort(oracle, P, E):
+    rng = np.random.default_rng(P + E)
+    keys = rng.integers(0, E, size=P).astype(np.int32)
+    if P > 10:
+        keys[keys == 1] = 0  # leave an expert empty
+    off, perm, inv = oracle.permute(keys, E)
+    assert np.array_equal(perm, np.argsort(keys, kind="stable").astype(np.int32))
+    assert np.array_equal(off, np.concatenate([[0], np.cumsum(np.bincount(keys, minlength=E))]))
+    assert np.array_equal(inv[perm], np.arange(P))
+    assert np.array_equal(perm[inv], np.arange(P))
+    payload = rng.standard_normal((P, 3))
+    assert np.array_equal(payload[perm][inv], payload)  # unpermute(permute(.)) = identity
+
+
+def test_permute_rejects_out_of_range_expert(oracle):
+    with pytest.raises(ValueError):
+        oracle.permute(np.array([0, 3], np.int32), 3)
+
+
+# ----------------------------------------------------------------- expert FFN (Sec. 3.1)
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_single_expert_layer_is_a_dense_swiglu_ffn(oracle, dtype):
+    cfg, w = _rand_layer(21, 12, 20, 1, dtype)
+    x = wl.normal_tensor(21, 1, (5, 12), 1.0, dtype)
+    y, idx, gate = oracle.forward(w, x, 1)
+    ref = _swiglu_torch(_f64(x), _f64(w["w_gate"][0]), _f64(w["w_up"][0]), _f64(w["w_down"][0]))
+    assert np.all(idx == 0) and np.all(gate == 1.0)
+    assert np.allclose(y, ref, rtol=1e-12, atol=1e-14)
+
+
+def test_ffn_zero_input_linearity_and_residual(oracle):
+    cfg, w = _rand_layer(22, 8, 12, 3)
+    x = wl.normal_tensor(22, 1, (4, 8), 1.0, "f32")
+    y0, _, _ = oracle.forward(w, np.zeros_like(x), 2)
+    assert np.all(y0 == 0.0)  # silu(0) = 0
+    y1, i1, _ = oracle.forward(w, x, 2)
+    w2 = dict(w)
+    w2["w_down"] = w["w_down"] * np.float32(2.0)
+    y2, i2, _ = oracle.forward(w2, x, 2)
+    assert np.array_equal(i1, i2) and np.allclose(y2, 2.0 * y1, rtol=1e-14)
+    yr, _, _ = oracle.forward(w, x, 2, residual=True)
+    assert np.allclose(yr, y1 + x.astype(np.float64), rtol=1e-15, atol=1e-16)
+
+
+def test_grouped_ffn_uses_each_groups_own_expert(oracle):
+    cfg, w = _rand_layer(23, 10, 14, 4, "bf16")
+    xp = wl.normal_tensor(23, 1, (9, 10), 1.0, "bf16")
+    off = np.array([0, 3, 3, 7, 9], np.int32)  # expert 1 empty
+    y = oracle.expert_ffn(w, xp, off)
+    for e in range(4):
+        rows = slice(off[e], off[e + 1])
+        ref = _swiglu_torch(_f64(xp[rows]), _f64(w["w_gate"][e]), _f64(w["w_up"][e]),
+                            _f64(w["w_down"][e]))
+        assert np.allclose(y[rows], ref, rtol=1e-12, atol=1e-14)
+
+
+# ----------------------------------------------------------------- whole layer
+
+def test_all_experts_active_with_uniform_gates_is_the_expert_average(oracle):
+    cfg, w = _rand_layer(31, 12, 16, 4)
+    w["router_w"] = np.zeros_like(w["router_w"])
+    x = wl.normal_tensor(31, 1, (6, 12), 1.0, "f32")
+    y, idx, gate = oracle.forward(w, x, 4)
+    outs = [_swiglu_torch(_f64(x), _f64(w["w_gate"][e]), _f64(w["w_up"][e]), _f64(w["w_down"][e]))
+            for e in range(4)]
+    assert np.allclose(y, np.mean(outs, axis=0), rtol=1e-12, atol=1e-14)
+
+
+def test_identical_experts_make_routing_irrelevant(oracle):
+    cfg, w = _rand_layer(32, 12, 16, 5, bias=True)
+    for n in ("w_gate", "w_up", "w_down"):
+        w[n] = np.ascontiguousarray(np.broadcast_to(w[n][:1], w[n].shape))
+    x = wl.normal_tensor(32, 1, (6, 12), 1.0, "f32")
+    y, idx, gate = oracle.forward(w, x, 2)
+    ref = _swiglu_torch(_f64(x), _f64(w["w_gate"][0]), _f64(w["w_up"][0]), _f64(w["w_down"][0]))
+    assert len(np.unique(idx)) > 1
+    assert np.allclose(y, ref, rtol=1e-12, atol=1e-14)
+
+
+def test_token_permutation_equivariance_is_bit_exact(oracle):
+    cfg, w = _rand_layer(33, 16, 24, 6, "bf16")
+    x = wl.normal_tensor(33, 1, (20, 16), 1.0, "bf16")
+    p = np.random.default_rng(3).permutation(20)
+    y, idx, gate = oracle.forward(w, x, 2)
+    yp, idxp, gatep = oracle.forward(w, np.ascontiguousarray(x[p]), 2)
+    assert np.array_equal(yp, y[p]) and np.array_equal(idxp, idx[p]) and np.array_equal(gatep, gate[p])
+
+
+def test_staged_pipeline_equals_direct_per_token_definition(oracle):
+    cfg, w = _rand_layer(34, 16, 24, 5, "f32", bias=True)
+    x = wl.normal_tensor(34, 1, (33, 16), 1.0, "f32")
+    k = 3
+    y, idx, gate = oracle.forward(w, x, k)
+    i2, g2, _, _ = oracle.route(x, w["router_w"], w["router_b"], k)
+    assert np.array_equal(idx, i2) and np.array_equal(gate, g2)
+    off, perm, inv = oracle.permute(i2, 5)
+    xp = np.ascontiguousarray(x[perm // k])
+    yp = oracle.expert_ffn(w, xp, off)
+    y2 = oracle.combine(yp, inv, g2)
+    assert np.allclose(y2, y, rtol=1e-13, atol=1e-15)
+    y3 = oracle.combine(yp, inv, g2, residual=x)
+    assert np.allclose(y3, y + x.astype(np.float64), rtol=1e-13, atol=1e-15)
+
+
+def test_tiny_layer_against_pure_python_brute_force(oracle):
+    T, d, F, E, k = 3, 4, 5, 3, 2
+    cfg, w = _rand_layer(35, d, F, E, bias=True)
+    cfg = wl.shrink(cfg, weight_std=0.7)
+    x = wl.normal_tensor(35, 1, (T, d), 1.0, "f32")
+    y, idx, gate = oracle.forward(w, x, k)
+    X = x.astype(float).tolist()
+    RW, RB = w["router_w"].astype(float).tolist(), w["router_b"].astype(float).tolist()
+    G, U, D = (w[n].astype(float).tolist() for n in ("w_gate", "w_up", "w_down"))
+    for t in range(T):
+        logit = [math.fsum(X[t][i] * RW[e][i] for i in range(d)) + RB[e] for e in range(E)]
+        m = max(logit)
+        ex = [math.exp(l - m) for l in logit]
+        prob = [v / math.fsum(ex) for v in ex]
+        sel = sorted(range(E), key=lambda e: (-logit[e], e))[:k]
+        den = math.fsum(prob[e] for e in sel)
+        out = [0.0] * d
+        for e in sel:
+            h = []
+            for f in range(F):
+                a = math.fsum(G[e][f][i] * X[t][i] for i in range(d))
+                b = math.fsum(U[e][f][i] * X[t][i] for i in range(d))
+                h.append(a / (1.0 + math.exp(-a)) * b)
+            for o in range(d):
+                out[o] += prob[e] / den * math.fsum(D[e][o][f] * h[f] for f in range(F))
+        assert list(idx[t]) == sel
+        assert np.allclose(y[t], out, rtol=1e-12, atol=1e-15)
+
+
+# ----------------------------------------------------------------- weight-decomposed experts (Eq. 1)
+
+def _materialised_layer_torch(w, x, idx, gate, shared_base):
+    """y from library matmuls with every expert matrix materialised as M0 + L R."""
+    xs = _f64(x)
+    T, k = idx.shape
+    y = np.zeros((T, xs.shape[1]))
+    mats = {}
+    for e in np.unique(idx):
+        m = []
+        for dn, Ln, Rn in (("w_gate", "lg", "rg"), ("w_up", "lu", "ru"), ("w_down", "ld", "rd")):
+            M = _f64(w[Ln][e]) @ _f64(w[Rn][e])
+            if shared_base:
+                M = M + _f64(w[dn][0])
+            m.append(M)
+        mats[int(e)] = m
+    for t in range(T):
+        for j in range(k):
+            g, u, dn = mats[int(idx[t, j])]
+            y[t] += gate[t, j] * _swiglu_torch(xs[t:t + 1], g, u, dn)[0]
+    return y
+
+
+@pytest.mark.parametrize("shared_base", [False, True])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_decomposed_experts_equal_their_materialised_matrices(oracle, dtype, shared_base):
+    cfg, w = _rand_layer(41, 12, 20, 4, dtype, r=6, shared_base=shared_base)
+    x = wl.normal_tensor(41, 1, (7, 12), 1.0, dtype)
+    y, idx, gate = oracle.forward(w, x, 2)
+    ref = _materialised_layer_torch(w, x, idx, gate, shared_base)
+    assert np.allclose(y, ref, rtol=1e-11, atol=1e-13)
+    # the staged grouped FFN takes the same factors
+    off, perm, inv = oracle.permute(idx, 4)
+    yp = oracle.expert_ffn(w, np.ascontiguousarray(x[perm // 2]), off)
+    assert np.allclose(oracle.combine(yp, inv, gate), y, rtol=1e-13, atol=1e-15)
+
+
+def test_full_rank_identity_factor_reduces_to_dense(oracle):
+    d, F, E = 8, 12, 3
+    cfg, w = _rand_layer(42, d, F, E)
+    x = wl.normal_tensor(42, 1, (5, d), 1.0, "f32")
+    eye = np.ascontiguousarray(np.broadcast_to(np.eye(d, dtype=np.float32), (E, d, d)))
+    wd = {n: None for n in w}
+    wd["router_w"] = w["router_w"]
+    wd["rg"], wd["lg"] = eye, w["w_gate"]        # gate: L = W_gate, R = I_d
+    wd["ru"], wd["lu"] = eye, w["w_up"]
+    wd["rd"], wd["ld"] = w["w_down"], eye        # down: L = I_d, R = W_down  (r = d)
+    y0, i0, _ = oracle.forward(w, x, 2)
+    y1, i1, _ = oracle.forward(wd, x, 2)
+    assert np.array_equal(i0, i1) and np.allclose(y1, y0, rtol=1e-14, atol=1e-16)
+
+
+def test_zero_factors_with_shared_base_reduce_to_the_shared_ffn(oracle):
+    cfg, w = _rand_layer(43, 10, 14, 4, r=3, shared_base=True)
+    for n in ("lg", "lu", "ld"):
+        w[n] = np.zeros_like(w[n])
+    x = wl.normal_tensor(43, 1, (6, 10), 1.0, "f32")
+    y, _, _ = oracle.forward(w, x, 2)
+    ref = _swiglu_torch(_f64(x), _f64(w["w_gate"][0]), _f64(w["w_up"][0]), _f64(w["w_down"][0]))
+    assert np.allclose(y, ref, rtol=1e-12, atol=1e-14)
+
+
+# ----------------------------------------------------------------- residual stack
+
+def test_stack_of_one_is_the_layer_plus_residual_and_zero_experts_are_identity(oracle):
+    cfg, w = _rand_layer(51, 12, 16, 4, "bf16")
+    x = wl.normal_tensor(51, 1, (5, 12), 1.0, "bf16")
+    y1, trace, xs = oracle.stack_forward([w], x, 2)
+    yr, idx, _ = oracle.forward(w, x, 2, residual=True)
+    assert np.array_equal(y1, yr) and np.array_equal(trace[0], idx)
+    assert np.array_equal(xs[0], _f64(x)) and np.array_equal(xs[1], y1)
+    wz = dict(w)
+    wz["w_down"] = np.zeros_like(w["w_down"])
+    yz, _, _ = oracle.stack_forward([wz, wz, wz], x, 2)
+    assert np.array_equal(yz, _f64(x))
+
+
+def test_stack_composes_layers_in_order(oracle):
+    cfg = wl.LayerConfig("t", 12, 16, 4, 2, "f32", 52, weight_std=0.3, router_std=0.3)
+    layers = [wl.make_layer_weights(cfg, layer=l) for l in range(3)]
+    x = wl.normal_tensor(52, 1, (4, 12), 1.0, "f32")
+    y, trace, xs = oracle.stack_forward(layers, x, 2)
+    cur = x.astype(np.float64)
+    for l, w in enumerate(layers):
+        # feed the fp64 state through a float32 copy only where exact: compare increments instead
+        y_l, _, _ = oracle.stack_forward([w], xs[l].astype(np.float32), 2)
+        if np.array_equal(xs[l].astype(np.float32).astype(np.float64), xs[l]):
+            assert np.allclose(y_l, xs[l + 1], rtol=1e-13)
+    assert np.array_equal(xs[0], cur) and np.array_equal(xs[3], y)
+    assert not np.array_equal(trace[0], trace[1])
+
+
+# ----------------------------------------------------------------- expert replacements (Eq. 4, Eq. 5)
+
+def _load_indicator(name):
+    m = np.loadtxt(os.path.join(GOLDEN, name), dtype=np.int64, comments="#")
+    assert m.shape == (8, 35)
+    return m
+
+
+@pytest.mark.parametrize("name,replacements", [("fig5_bles.txt", 11), ("fig5_moe.txt", 21)])
+def test_expert_replacements_reproduce_the_papers_worked_example(oracle, name, replacements):
+    m = _load_indicator(name)
+    assert np.all(m.sum(0) == 2)            # two active experts for every token
+    assert int((m.sum(1) > 0).sum()) == 6   # "6 out of the 8 experts"
+    S = np.stack([np.flatnonzero(m[:, t]) for t in range(35)]).astype(np.int32)[None]
+    H, He = oracle.expert_replacements(S, 8)
+    assert H % 2 == 0 and H // 2 == replacements  # every replacement is counted twice
+    assert np.array_equal(He, np.abs(np.diff(m, axis=1)).sum(1))
+
+
+def test_expert_replacements_closed_forms(oracle):
+    const = np.tile(np.array([[2, 5]], np.int32), (1, 10, 1))
+    assert oracle.expert_replacements(const, 8)[0] == 0
+    alt = np.array([[[0, 1], [2, 3]] * 5], np.int32)  # full swap at each of 9 steps
+    H, He = oracle.expert_replacements(alt, 4)
+    assert H == 9 * 4 and np.all(He == 9)
+    two = np.concatenate([const, const], axis=0)  # batches do not interact
+    assert oracle.expert_replacements(two, 8)[0] == 0
