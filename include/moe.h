@@ -40,6 +40,9 @@
 extern "C" {
 #endif
 
+/* exported from the shared library (which is built with hidden default visibility) */
+#define MOE_API __attribute__((visibility("default")))
+
 enum { MOE_F32 = 0, MOE_BF16 = 1 };
 
 enum {
@@ -103,7 +106,7 @@ typedef struct moe_weights {
  *   topk_gate  [T, k]  fp32           out
  *   probs      [T, E]  fp32 or NULL   out (full softmax, for routing statistics)
  */
-int moe_route(const moe_shape* shape, const void* x, const float* router_w,
+MOE_API int moe_route(const moe_shape* shape, const void* x, const float* router_w,
               const float* router_b, int32_t* topk_idx, float* topk_gate, float* probs,
               void* stream);
 
@@ -118,7 +121,7 @@ int moe_route(const moe_shape* shape, const void* x, const float* router_w,
  *                  pass both NULL to skip it.
  * Every topk_idx value must lie in [0, E).  workspace: moe_workspace_bytes(shape).
  */
-int moe_permute(const moe_shape* shape, const int32_t* topk_idx, int32_t* expert_offsets,
+MOE_API int moe_permute(const moe_shape* shape, const int32_t* topk_idx, int32_t* expert_offsets,
                 int32_t* perm, int32_t* inv_perm, const void* x, void* x_perm,
                 void* workspace, size_t workspace_bytes, void* stream);
 
@@ -131,7 +134,7 @@ int moe_permute(const moe_shape* shape, const int32_t* topk_idx, int32_t* expert
  * (the F-wide hidden vector and the rank-r intermediates) are rounded to bf16.
  *   x_perm [P, d] in, y_perm [P, d] out (act_dtype); expert_offsets [E+1] as above.
  */
-int moe_expert_ffn(const moe_shape* shape, const moe_weights* weights, const void* x_perm,
+MOE_API int moe_expert_ffn(const moe_shape* shape, const moe_weights* weights, const void* x_perm,
                    const int32_t* expert_offsets, void* y_perm, void* workspace,
                    size_t workspace_bytes, void* stream);
 
@@ -140,7 +143,7 @@ int moe_expert_ffn(const moe_shape* shape, const moe_weights* weights, const voi
  * summed in fp32 in ascending j (Sec. 1: the gate sets each expert's contribution).
  *   residual [T, d] act_dtype or NULL; y [T, d] act_dtype out.
  */
-int moe_combine(const moe_shape* shape, const void* y_perm, const int32_t* inv_perm,
+MOE_API int moe_combine(const moe_shape* shape, const void* y_perm, const int32_t* inv_perm,
                 const float* topk_gate, const void* residual, void* y, void* stream);
 
 /*
@@ -150,7 +153,7 @@ int moe_combine(const moe_shape* shape, const void* y_perm, const int32_t* inv_p
  * topk_idx / topk_gate ([T,k]) are optional outputs (NULL to skip) and equal what
  * moe_route returns.  With MOE_FLAG_RESIDUAL, y = x + layer(x); y must not alias x.
  */
-int moe_forward(const moe_shape* shape, const moe_weights* weights, const void* x, void* y,
+MOE_API int moe_forward(const moe_shape* shape, const moe_weights* weights, const void* x, void* y,
                 int32_t* topk_idx, float* topk_gate, void* workspace, size_t workspace_bytes,
                 void* stream);
 
@@ -161,15 +164,15 @@ int moe_forward(const moe_shape* shape, const moe_weights* weights, const void* 
  * topk_trace ([n_layers, T, k] int32) is optional.  shape.flags' residual bit is
  * implied.  workspace: moe_workspace_bytes(shape).
  */
-int moe_stack_forward(const moe_shape* shape, const moe_weights* layers, int32_t n_layers,
+MOE_API int moe_stack_forward(const moe_shape* shape, const moe_weights* layers, int32_t n_layers,
                       const void* x, void* y, int32_t* topk_trace, void* workspace,
                       size_t workspace_bytes, void* stream);
 
 /* Bytes of workspace that any entry point above needs for this shape (0 if invalid). */
-size_t moe_workspace_bytes(const moe_shape* shape);
+MOE_API size_t moe_workspace_bytes(const moe_shape* shape);
 
 /* Static, NUL-terminated description of a status code. */
-const char* moe_status_string(int status);
+MOE_API const char* moe_status_string(int status);
 
 #ifdef __cplusplus
 }

@@ -1,0 +1,8 @@
+"""MI355X-native sparse MoE feed-forward layer (CoSMoEs, arXiv 2503.00245): HIP kernels for
+gfx950 behind the C ABI of include/moe.h, plus a ctypes binding of the same names."""
+from .binding import (  # noqa: F401
+    EXPORTS, FLAG_RESIDUAL, FLAG_SHARED_BASE, LIB_PATH, MOE_BF16, MOE_F32, MoeError, MoeShape,
+    MoeWeights, alloc_workspace, lib, make_shape, make_weights, moe_combine, moe_expert_ffn,
+    moe_forward, moe_permute, moe_route, moe_stack_forward, moe_workspace_bytes, shape_for,
+    status_string,
+)

@@ -1,0 +1,178 @@
+"""ctypes binding of libmoe_mi355x.so: the entry points of include/moe.h under the same names.
+
+Argument marshalling only: tensors are torch CUDA(HIP) tensors used for device memory
+and the current stream; every step of the layer runs in the library's kernels.  There
+is no fallback: a missing library, or a non-zero status, raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmoe_mi355x.so")
+
+MOE_F32, MOE_BF16 = 0, 1
+FLAG_SHARED_BASE, FLAG_RESIDUAL = 1, 2
+WEIGHT_FIELDS = ("router_w", "router_b", "w_gate", "w_up", "w_down",
+                 "rg", "ru", "rd", "lg", "lu", "ld")
+EXPORTS = ("moe_route", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_forward",
+           "moe_stack_forward", "moe_workspace_bytes", "moe_status_string")
+
+
+class MoeShape(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_tokens", "d_model", "d_ff", "n_experts", "top_k",
+                                          "rank", "act_dtype", "flags")]
+
+
+class MoeWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in WEIGHT_FIELDS]
+
+
+class MoeError(RuntimeError):
+    def __init__(self, fn: str, status: int):
+        self.status = status
+        super().__init__(f"{fn} failed: {status_string(status)} ({status})")
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded shared library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python __graft_entry__.py` "
+                              "(or paper_2503_00245_amd/build.py) to compile the HIP library")
+        L = C.CDLL(LIB_PATH)
+        L.moe_workspace_bytes.restype = C.c_size_t
+        L.moe_workspace_bytes.argtypes = [C.POINTER(MoeShape)]
+        L.moe_status_string.restype = C.c_char_p
+        L.moe_status_string.argtypes = [C.c_int]
+        vp, sz = C.c_void_p, C.c_size_t
+        sp = C.POINTER(MoeShape)
+        wp = C.POINTER(MoeWeights)
+        L.moe_route.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp]
+        L.moe_permute.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.moe_expert_ffn.argtypes = [sp, wp, vp, vp, vp, vp, sz, vp]
+        L.moe_combine.argtypes = [sp, vp, vp, vp, vp, vp, vp]
+        L.moe_forward.argtypes = [sp, wp, vp, vp, vp, vp, vp, sz, vp]
+        L.moe_stack_forward.argtypes = [sp, wp, C.c_int32, vp, vp, vp, vp, sz, vp]
+        for fn in ("moe_route", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_forward",
+                   "moe_stack_forward"):
+            getattr(L, fn).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().moe_status_string(int(status)).decode()
+
+
+def _check(fn: str, status: int) -> None:
+    if status != 0:
+        raise MoeError(fn, status)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_contiguous():
+        raise ValueError("tensors handed to the library must be contiguous")
+    return t.data_ptr()
+
+
+def _stream(device) -> int:
+    return torch.cuda.current_stream(device).cuda_stream
+
+
+def _act_dtype(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return MOE_F32
+    if t.dtype == torch.bfloat16:
+        return MOE_BF16
+    raise TypeError(f"activation dtype must be float32 or bfloat16, got {t.dtype}")
+
+
+def make_shape(n_tokens, d_model, d_ff, n_experts, top_k, rank=0, act_dtype=MOE_BF16,
+               flags=0) -> MoeShape:
+    return MoeShape(n_tokens, d_model, d_ff, n_experts, top_k, rank, act_dtype, flags)
+
+
+def shape_for(weights: Dict[str, Optional[torch.Tensor]], n_tokens: int, top_k: int,
+              act_dtype: int, residual: bool = False) -> MoeShape:
+    """Shape struct read off a weights dict (keys as in the C struct)."""
+    E, d = weights["router_w"].shape
+    if weights.get("rg") is not None:
+        r = weights["rg"].shape[1]
+        F = weights["lg"].shape[1]
+    else:
+        r = 0
+        F = weights["w_gate"].shape[1]
+    flags = (FLAG_SHARED_BASE if (r > 0 and weights.get("w_gate") is not None) else 0) | \
+            (FLAG_RESIDUAL if residual else 0)
+    return make_shape(n_tokens, d, F, E, top_k, r, act_dtype, flags)
+
+
+def make_weights(weights: Dict[str, Optional[torch.Tensor]]) -> MoeWeights:
+    w = MoeWeights()
+    for name in WEIGHT_FIELDS:
+        setattr(w, name, _ptr(weights.get(name)))
+    return w
+
+
+def moe_workspace_bytes(shape: MoeShape) -> int:
+    return int(lib().moe_workspace_bytes(C.byref(shape)))
+
+
+def alloc_workspace(shape: MoeShape, device) -> torch.Tensor:
+    n = moe_workspace_bytes(shape)
+    if n == 0:
+        raise MoeError("moe_workspace_bytes", -1)
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def moe_route(shape: MoeShape, x, router_w, router_b, topk_idx, topk_gate, probs=None) -> None:
+    _check("moe_route", lib().moe_route(C.byref(shape), _ptr(x), _ptr(router_w), _ptr(router_b),
+                                        _ptr(topk_idx), _ptr(topk_gate), _ptr(probs),
+                                        _stream(x.device)))
+
+
+def moe_permute(shape: MoeShape, topk_idx, expert_offsets, perm, inv_perm, x=None, x_perm=None,
+                workspace=None) -> None:
+    _check("moe_permute", lib().moe_permute(
+        C.byref(shape), _ptr(topk_idx), _ptr(expert_offsets), _ptr(perm), _ptr(inv_perm), _ptr(x),
+        _ptr(x_perm), _ptr(workspace), 0 if workspace is None else workspace.numel(),
+        _stream(expert_offsets.device)))
+
+
+def moe_expert_ffn(shape: MoeShape, weights: MoeWeights, x_perm, expert_offsets, y_perm,
+                   workspace) -> None:
+    _check("moe_expert_ffn", lib().moe_expert_ffn(
+        C.byref(shape), C.byref(weights), _ptr(x_perm), _ptr(expert_offsets), _ptr(y_perm),
+        _ptr(workspace), workspace.numel(), _stream(y_perm.device)))
+
+
+def moe_combine(shape: MoeShape, y_perm, inv_perm, topk_gate, residual, y) -> None:
+    _check("moe_combine", lib().moe_combine(C.byref(shape), _ptr(y_perm), _ptr(inv_perm),
+                                            _ptr(topk_gate), _ptr(residual), _ptr(y),
+                                            _stream(y.device)))
+
+
+def moe_forward(shape: MoeShape, weights: MoeWeights, x, y, topk_idx=None, topk_gate=None,
+                workspace=None) -> None:
+    _check("moe_forward", lib().moe_forward(
+        C.byref(shape), C.byref(weights), _ptr(x), _ptr(y), _ptr(topk_idx), _ptr(topk_gate),
+        _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream(y.device)))
+
+
+def moe_stack_forward(shape: MoeShape, layers: Sequence[MoeWeights], x, y, topk_trace=None,
+                      workspace=None) -> None:
+    arr = (MoeWeights * len(layers))(*layers)
+    _check("moe_stack_forward", lib().moe_stack_forward(
+        C.byref(shape), arr, len(layers), _ptr(x), _ptr(y), _ptr(topk_trace), _ptr(workspace),
+        0 if workspace is None else workspace.numel(), _stream(y.device)))

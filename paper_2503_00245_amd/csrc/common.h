@@ -1,0 +1,89 @@
+// Shared device/host helpers of the gfx950 MoE library (internal; not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "moe.h"
+
+namespace moe {
+
+constexpr int kWave = 64;        // CDNA wavefront width
+constexpr int kMaxExperts = 64;  // one lane per expert in the router's selection step
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// ---- storage-type traits: VEC elements per 16-byte load -------------------------------
+template <typename T>
+struct Store;
+template <>
+struct Store<float> {
+    static constexpr int VEC = 4;
+    typedef f32x4 vec_t;
+    static __device__ __forceinline__ float get(const vec_t& v, int i) { return v[i]; }
+    static __device__ __forceinline__ float to_f32(float v) { return v; }
+    static __device__ __forceinline__ float from_f32(float v) { return v; }
+};
+template <>
+struct Store<bf16_t> {
+    static constexpr int VEC = 8;
+    typedef bf16x8 vec_t;
+    static __device__ __forceinline__ float get(const vec_t& v, int i) { return (float)v[i]; }
+    static __device__ __forceinline__ float to_f32(bf16_t v) { return (float)v; }
+    static __device__ __forceinline__ bf16_t from_f32(float v) { return (bf16_t)v; }  // RNE
+};
+
+// ---- wavefront reductions (butterfly over all 64 lanes; every lane gets the result) ----
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
+    return v;
+}
+
+__device__ __forceinline__ float silu_f32(float z) { return z / (1.0f + __expf(-z)); }
+
+// ---- host side ---------------------------------------------------------------------------
+inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+
+inline int launch_status() { return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_LAUNCH; }
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline size_t elt_size(int act_dtype) { return act_dtype == MOE_F32 ? 4 : 2; }
+
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Shape check shared by every entry point: MOE_OK, MOE_ERR_INVALID or MOE_ERR_UNSUPPORTED.
+int validate_shape(const moe_shape* s);
+
+// ---- per-stage launchers (each file owns its kernels) ---------------------------------------
+int launch_route(const moe_shape& s, const void* x, const float* rw, const float* rb,
+                 int32_t* topk_idx, float* topk_gate, float* probs, hipStream_t st);
+
+size_t permute_scratch_bytes(int P, int E);
+int launch_permute(int P, int E, const int32_t* topk_idx, int32_t* offsets, int32_t* perm,
+                   int32_t* inv_perm, void* scratch, hipStream_t st);
+int launch_gather_rows(const moe_shape& s, const int32_t* perm, const void* x, void* x_perm,
+                       hipStream_t st);
+
+int launch_combine(const moe_shape& s, const void* y_perm, const int32_t* inv_perm,
+                   const float* topk_gate, const void* residual, void* y, hipStream_t st);
+
+// Grouped expert FFN on P sorted rows.  a_row_map/a_row_div: optional gather of the input
+// rows (row of sorted slot s is x[a_row_map[s] / a_row_div]); NULL = x is already grouped.
+size_t ffn_scratch_bytes(const moe_shape& s);
+int launch_expert_ffn(const moe_shape& s, const moe_weights& w, const void* x,
+                      const int32_t* a_row_map, int a_row_div, const int32_t* offsets,
+                      void* y_perm, void* scratch, hipStream_t st);
+
+// Single-token layer: experts chosen on the device from topk_idx, weights streamed once.
+size_t decode_scratch_bytes(const moe_shape& s);
+int launch_decode_ffn(const moe_shape& s, const moe_weights& w, const void* x,
+                      const int32_t* topk_idx, const float* topk_gate, void* y, void* scratch,
+                      hipStream_t st);
+
+}  // namespace moe

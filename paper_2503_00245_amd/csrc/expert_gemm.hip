@@ -1,0 +1,409 @@
+// Grouped expert GEMMs for prefill: every expert multiplies its own contiguous group of
+// sorted rows by its own matrices (Sec. 2.1), with the SwiGLU activation fused into the
+// gate/up product's epilogue and weight-decomposed experts (Sec. 2.2, Eq. 1) expressed
+// as extra K-segments accumulated into the same output tile.
+//
+// One generic problem:   C[s, n] = epi( sum_seg  A_seg[row(s), :] . B_seg[e(s)][n, :] )
+//   PLAIN   one accumulator, C = acc
+//   SWIGLU  two accumulators over (A0,B0) and (A1,B1); C = silu(acc0) * acc1
+// A and B are both K-contiguous ("NT" GEMM), the natural layout of activations [rows, in]
+// and linear-layer weights [out, in], and exactly what an MFMA lane wants: 8 consecutive
+// k of one row per 16-byte read.
+//
+// bf16 kernel: 256 threads = 4 waves, block tile BM x BN x 64, wave tile WM x WN built
+// from v_mfma_f32_32x32x16_bf16, fp32 accumulators in registers.  Global -> registers ->
+// LDS with a two-stage LDS ring (loads of tile kt+1 are in flight while tile kt is
+// multiplied).  LDS rows are 128 bytes (64 bf16) with the 16-byte chunk index XOR-ed by
+// (row >> 1) & 7, which spreads both the row-wise fills and the column-of-rows MFMA
+// operand reads over all banks.  Tiles are enumerated n-tile major / m-tile minor and the
+// workgroup id is remapped so that consecutive tiles (which share the same weight tile)
+// land on the same XCD and hit in its L2.
+//
+// fp32 problems (correctness-only configuration) use a plain LDS-tiled FMA kernel.
+#include "common.h"
+
+namespace moe {
+
+struct GemmSeg {
+    const void* A0;     // [*, K]
+    const void* A1;     // A of the second accumulator (SWIGLU); may equal A0
+    const void* B0;     // [Eb, N, K]
+    const void* B1;
+    long long strideB;  // elements between experts; 0 = shared by all experts
+    int K;
+    int gather;         // 1: the A row of sorted slot s is row_map[s] / row_div
+};
+
+struct GemmArgs {
+    GemmSeg seg[2];
+    int nseg;
+    void* C;            // [P, N]
+    int N;
+    const int32_t* offsets;  // [E+1]
+    const int32_t* row_map;  // [P] or NULL
+    int row_div;
+    int E;
+    int P;
+    int m_tiles_max;
+    int n_tiles;
+};
+
+// m-tile index (over all experts, in expert order) -> expert and row range
+__device__ __forceinline__ bool find_m_tile(const int32_t* __restrict__ offsets, int E, int BM,
+                                            int mt, int& e_out, int& row0, int& row_end) {
+    int acc = 0;
+    int prev = offsets[0];
+    for (int e = 0; e < E; ++e) {
+        const int next = offsets[e + 1];
+        const int tiles = (next - prev + BM - 1) / BM;
+        if (mt < acc + tiles) {
+            e_out = e;
+            row0 = prev + (mt - acc) * BM;
+            row_end = next;
+            return true;
+        }
+        acc += tiles;
+        prev = next;
+    }
+    return false;
+}
+
+__device__ __forceinline__ int src_row(const GemmArgs& g, const GemmSeg& sg, int s) {
+    if (!sg.gather) return s;
+    const int p = min(max(g.row_map[s], 0), g.P - 1);
+    return p / g.row_div;
+}
+
+// ============================================================================= bf16 MFMA
+constexpr int BK = 64;  // k elements per LDS tile row = 128 bytes = 8 chunks of 16 bytes
+
+__device__ __forceinline__ int lds_off(int row, int chunk) {
+    return row * (BK * 2) + ((chunk ^ ((row >> 1) & 7)) << 4);
+}
+
+template <int BM, int BN, int WM, int WN, bool SWIGLU, bool DUAL_A>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmArgs g) {
+    constexpr int WAVES_N = BN / WN;
+    static_assert((BM / WM) * WAVES_N == 4, "four waves per workgroup");
+    constexpr int MT = WM / 32, NT = WN / 32;
+    static_assert(!SWIGLU || NT % 2 == 0, "gate and up fragments pair up");
+    constexpr int AI = BM / 32, BI = BN / 32;  // 16-byte chunks per thread per tile
+    constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
+    constexpr int STAGE = A_BYTES * (DUAL_A ? 2 : 1) + B_BYTES;
+    extern __shared__ __align__(16) char smem[];
+
+    // ---- which tile --------------------------------------------------------------------------
+    const int total = g.m_tiles_max * g.n_tiles;
+    const int per_xcd = (gridDim.x + 7) / 8;
+    const int L = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (L >= total) return;
+    const int mt = L % g.m_tiles_max;
+    const int nt = L / g.m_tiles_max;
+    int e, row0, row_end;
+    if (!find_m_tile(g.offsets, g.E, BM, mt, e, row0, row_end)) return;
+    constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;  // output columns per block
+    const int n0 = nt * BN_OUT;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const int ld_row = tid >> 3, ld_chunk = tid & 7;
+
+    f32x16 acc[MT][NT];
+#pragma unroll
+    for (int mi = 0; mi < MT; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NT; ++ni)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
+
+    for (int sidx = 0; sidx < g.nseg; ++sidx) {
+        const GemmSeg& sg = g.seg[sidx];
+        const int K = sg.K;
+        const bool dual = DUAL_A && sg.A1 != sg.A0;
+        const bf16_t* A0 = static_cast<const bf16_t*>(sg.A0);
+        const bf16_t* A1 = static_cast<const bf16_t*>(sg.A1);
+        const bf16_t* B0 = static_cast<const bf16_t*>(sg.B0) + (size_t)e * sg.strideB;
+        const bf16_t* B1 = SWIGLU ? static_cast<const bf16_t*>(sg.B1) + (size_t)e * sg.strideB : B0;
+
+        // element offsets of this thread's rows (-1: outside the group / matrix -> zeros)
+        long long aoff[AI], boff[BI];
+#pragma unroll
+        for (int i = 0; i < AI; ++i) {
+            const int s = row0 + ld_row + 32 * i;
+            aoff[i] = s < row_end ? (long long)src_row(g, sg, s) * K : -1;
+        }
+#pragma unroll
+        for (int i = 0; i < BI; ++i) {
+            const int j = ld_row + 32 * i;
+            const int n = SWIGLU ? n0 + (j % (BN / 2)) : n0 + j;
+            boff[i] = n < g.N ? (long long)n * K : -1;
+        }
+
+        bf16x8 ra[AI], ra1[DUAL_A ? AI : 1], rb[BI];
+        auto load_tile = [&](int k0) {
+            const int kk = k0 + ld_chunk * 8;
+            const bool kin = kk < K;
+#pragma unroll
+            for (int i = 0; i < AI; ++i) {
+                ra[i] = bf16x8{};
+                if (kin && aoff[i] >= 0) ra[i] = *reinterpret_cast<const bf16x8*>(A0 + aoff[i] + kk);
+                if (DUAL_A) {
+                    ra1[i] = bf16x8{};
+                    if (dual && kin && aoff[i] >= 0)
+                        ra1[i] = *reinterpret_cast<const bf16x8*>(A1 + aoff[i] + kk);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < BI; ++i) {
+                rb[i] = bf16x8{};
+                const bf16_t* B = (SWIGLU && i >= BI / 2) ? B1 : B0;
+                if (kin && boff[i] >= 0) rb[i] = *reinterpret_cast<const bf16x8*>(B + boff[i] + kk);
+            }
+        };
+        auto store_tile = [&](int stage) {
+            char* base = smem + stage * STAGE;
+#pragma unroll
+            for (int i = 0; i < AI; ++i) {
+                *reinterpret_cast<bf16x8*>(base + lds_off(ld_row + 32 * i, ld_chunk)) = ra[i];
+                if (DUAL_A && dual)
+                    *reinterpret_cast<bf16x8*>(base + A_BYTES + lds_off(ld_row + 32 * i, ld_chunk)) = ra1[i];
+            }
+            char* bb = base + A_BYTES * (DUAL_A ? 2 : 1);
+#pragma unroll
+            for (int i = 0; i < BI; ++i)
+                *reinterpret_cast<bf16x8*>(bb + lds_off(ld_row + 32 * i, ld_chunk)) = rb[i];
+        };
+
+        const int nk = (K + BK - 1) / BK;
+        __syncthreads();  // previous segment's readers are done with both stages
+        load_tile(0);
+        store_tile(0);
+        __syncthreads();
+        for (int kt = 0; kt < nk; ++kt) {
+            const int stage = kt & 1;
+            if (kt + 1 < nk) load_tile((kt + 1) * BK);
+            const char* base = smem + stage * STAGE;
+            const char* a0b = base;
+            const char* a1b = (DUAL_A && dual) ? base + A_BYTES : base;
+            const char* bb = base + A_BYTES * (DUAL_A ? 2 : 1);
+#pragma unroll
+            for (int ks = 0; ks < BK / 16; ++ks) {
+                const int chunk = ks * 2 + (lane >> 5);
+                bf16x8 fa[MT], fa1[DUAL_A ? MT : 1], fb[NT];
+#pragma unroll
+                for (int mi = 0; mi < MT; ++mi) {
+                    const int r = wm * WM + mi * 32 + (lane & 31);
+                    fa[mi] = *reinterpret_cast<const bf16x8*>(a0b + lds_off(r, chunk));
+                    if (DUAL_A) fa1[mi] = *reinterpret_cast<const bf16x8*>(a1b + lds_off(r, chunk));
+                }
+#pragma unroll
+                for (int ni = 0; ni < NT; ++ni) {
+                    int r;
+                    if (SWIGLU)
+                        r = (ni < NT / 2 ? 0 : BN / 2) + wn * (WN / 2) + (ni % (NT / 2)) * 32 + (lane & 31);
+                    else
+                        r = wn * WN + ni * 32 + (lane & 31);
+                    fb[ni] = *reinterpret_cast<const bf16x8*>(bb + lds_off(r, chunk));
+                }
+#pragma unroll
+                for (int mi = 0; mi < MT; ++mi)
+#pragma unroll
+                    for (int ni = 0; ni < NT; ++ni) {
+                        const bf16x8 av = (DUAL_A && SWIGLU && ni >= NT / 2) ? fa1[mi] : fa[mi];
+                        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, fb[ni], acc[mi][ni], 0, 0, 0);
+                    }
+            }
+            if (kt + 1 < nk) store_tile(stage ^ 1);
+            __syncthreads();
+        }
+    }
+
+    // ---- epilogue: accumulator element i of a 32x32 block sits at
+    //      row (i/4)*8 + (lane/32)*4 + i%4, column lane%32 ---------------------------------------
+    bf16_t* C = static_cast<bf16_t*>(g.C);
+#pragma unroll
+    for (int mi = 0; mi < MT; ++mi) {
+#pragma unroll
+        for (int ni = 0; ni < (SWIGLU ? NT / 2 : NT); ++ni) {
+            const int col = n0 + wn * (SWIGLU ? WN / 2 : WN) + ni * 32 + (lane & 31);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int row = row0 + wm * WM + mi * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
+                if (row < row_end && col < g.N) {
+                    float v = acc[mi][ni][i];
+                    if (SWIGLU) v = silu_f32(v) * acc[mi][ni + NT / 2][i];
+                    C[(size_t)row * g.N + col] = (bf16_t)v;
+                }
+            }
+        }
+    }
+}
+
+// ============================================================================= generic tiled FMA
+// 64 x 64 output tile, 256 threads, 4 x 4 outputs each, K stepped by 16 through LDS.
+template <typename T, bool SWIGLU>
+__global__ __launch_bounds__(256) void gemm_simple_kernel(const GemmArgs g) {
+    constexpr int TM = 64, TN = 64, TK = 16;
+    __shared__ float sA0[TK][TM + 1], sA1[TK][TM + 1], sB0[TK][TN + 1], sB1[TK][TN + 1];
+    const int mt = blockIdx.x % g.m_tiles_max;
+    const int nt = blockIdx.x / g.m_tiles_max;
+    int e, row0, row_end;
+    if (!find_m_tile(g.offsets, g.E, TM, mt, e, row0, row_end)) return;
+    const int n0 = nt * TN;
+    const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
+    float acc0[4][4] = {}, acc1[4][4] = {};
+    for (int sidx = 0; sidx < g.nseg; ++sidx) {
+        const GemmSeg& sg = g.seg[sidx];
+        const T* A0 = static_cast<const T*>(sg.A0);
+        const T* A1 = static_cast<const T*>(sg.A1);
+        const T* B0 = static_cast<const T*>(sg.B0) + (size_t)e * sg.strideB;
+        const T* B1 = SWIGLU ? static_cast<const T*>(sg.B1) + (size_t)e * sg.strideB : B0;
+        for (int k0 = 0; k0 < sg.K; k0 += TK) {
+            __syncthreads();
+            for (int i = threadIdx.x; i < TM * TK; i += 256) {
+                const int r = i / TK, kk = i % TK;
+                const int s = row0 + r;
+                const bool ok = s < row_end && k0 + kk < sg.K;
+                const size_t off = ok ? (size_t)src_row(g, sg, s) * sg.K + k0 + kk : 0;
+                sA0[kk][r] = ok ? Store<T>::to_f32(A0[off]) : 0.f;
+                if (SWIGLU) sA1[kk][r] = ok ? Store<T>::to_f32(A1[off]) : 0.f;
+                const int n = n0 + r;
+                const bool okb = n < g.N && k0 + kk < sg.K;
+                const size_t boff = okb ? (size_t)n * sg.K + k0 + kk : 0;
+                sB0[kk][r] = okb ? Store<T>::to_f32(B0[boff]) : 0.f;
+                if (SWIGLU) sB1[kk][r] = okb ? Store<T>::to_f32(B1[boff]) : 0.f;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int kk = 0; kk < TK; ++kk) {
+#pragma unroll
+                for (int a = 0; a < 4; ++a)
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        acc0[a][b] = fmaf(sA0[kk][ty * 4 + a], sB0[kk][tx * 4 + b], acc0[a][b]);
+                        if (SWIGLU)
+                            acc1[a][b] = fmaf(sA1[kk][ty * 4 + a], sB1[kk][tx * 4 + b], acc1[a][b]);
+                    }
+            }
+        }
+    }
+    T* C = static_cast<T*>(g.C);
+    for (int a = 0; a < 4; ++a)
+        for (int b = 0; b < 4; ++b) {
+            const int row = row0 + ty * 4 + a, col = n0 + tx * 4 + b;
+            if (row < row_end && col < g.N) {
+                const float v = SWIGLU ? silu_f32(acc0[a][b]) * acc1[a][b] : acc0[a][b];
+                C[(size_t)row * g.N + col] = Store<T>::from_f32(v);
+            }
+        }
+}
+
+// ============================================================================= host side
+template <int BM, int BN, int WM, int WN, bool SWIGLU, bool DUAL_A>
+static int launch_bf16(GemmArgs& g, hipStream_t st) {
+    constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;
+    g.m_tiles_max = g.P / BM + g.E;
+    g.n_tiles = (g.N + BN_OUT - 1) / BN_OUT;
+    const int total = g.m_tiles_max * g.n_tiles;
+    const int grid = (total + 7) / 8 * 8;
+    constexpr size_t lds = 2 * ((size_t)BM * BK * 2 * (DUAL_A ? 2 : 1) + (size_t)BN * BK * 2);
+    auto kern = gemm_bf16_kernel<BM, BN, WM, WN, SWIGLU, DUAL_A>;
+    static bool attr_set = false;
+    if (lds > 32 * 1024 && !attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+            return MOE_ERR_LAUNCH;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, g);
+    return launch_status();
+}
+
+template <typename T, bool SWIGLU>
+static int launch_simple(GemmArgs& g, hipStream_t st) {
+    g.m_tiles_max = g.P / 64 + g.E;
+    g.n_tiles = (g.N + 63) / 64;
+    hipLaunchKernelGGL((gemm_simple_kernel<T, SWIGLU>), dim3(g.m_tiles_max * g.n_tiles), dim3(256),
+                       0, st, g);
+    return launch_status();
+}
+
+static int run_gemm(const moe_shape& s, GemmArgs& g, bool swiglu, hipStream_t st) {
+    if (g.P == 0) return MOE_OK;
+    if (s.act_dtype == MOE_F32)
+        return swiglu ? launch_simple<float, true>(g, st) : launch_simple<float, false>(g, st);
+    bool dual = false;
+    for (int i = 0; i < g.nseg; ++i) dual |= swiglu && g.seg[i].A1 != g.seg[i].A0;
+    if (swiglu)
+        return dual ? launch_bf16<128, 128, 64, 64, true, true>(g, st)
+                    : launch_bf16<128, 128, 64, 64, true, false>(g, st);
+    return launch_bf16<128, 128, 64, 64, false, false>(g, st);
+}
+
+// scratch: h [P,F], then (rank > 0) tg, tu, td [P,r], all in the activation type
+size_t ffn_scratch_bytes(const moe_shape& s) {
+    const size_t P = (size_t)s.n_tokens * s.top_k, es = elt_size(s.act_dtype);
+    return round_up(P * s.d_ff * es, 256) + 3 * round_up(P * s.rank * es, 256);
+}
+
+int launch_expert_ffn(const moe_shape& s, const moe_weights& w, const void* x,
+                      const int32_t* a_row_map, int a_row_div, const int32_t* offsets,
+                      void* y_perm, void* scratch, hipStream_t st) {
+    const int d = s.d_model, F = s.d_ff, r = s.rank, E = s.n_experts;
+    const int P = s.n_tokens * s.top_k;
+    if (P == 0) return MOE_OK;
+    const size_t es = elt_size(s.act_dtype);
+    char* sc = static_cast<char*>(scratch);
+    void* h = sc;
+    sc += round_up((size_t)P * F * es, 256);
+    void* tg = sc;
+    sc += round_up((size_t)P * r * es, 256);
+    void* tu = sc;
+    sc += round_up((size_t)P * r * es, 256);
+    void* td = sc;
+    const bool base = (r == 0) || (s.flags & MOE_FLAG_SHARED_BASE);
+    const int gather = a_row_map ? 1 : 0;
+    int rc;
+    auto fresh = [&]() {
+        GemmArgs g{};
+        g.offsets = offsets; g.row_map = a_row_map; g.row_div = a_row_div > 0 ? a_row_div : 1;
+        g.E = E; g.P = P;
+        return g;
+    };
+    if (r > 0) {  // tg = x R_g^T, tu = x R_u^T   [P, r]
+        GemmArgs g = fresh();
+        g.nseg = 1; g.N = r; g.C = tg;
+        g.seg[0] = GemmSeg{x, x, w.rg, w.rg, (long long)r * d, d, gather};
+        if ((rc = run_gemm(s, g, false, st)) != MOE_OK) return rc;
+        g = fresh();
+        g.nseg = 1; g.N = r; g.C = tu;
+        g.seg[0] = GemmSeg{x, x, w.ru, w.ru, (long long)r * d, d, gather};
+        if ((rc = run_gemm(s, g, false, st)) != MOE_OK) return rc;
+    }
+    {  // h = silu(M_gate x) * (M_up x)   [P, F]
+        GemmArgs g = fresh();
+        int ns = 0;
+        if (base) g.seg[ns++] = GemmSeg{x, x, w.w_gate, w.w_up, r == 0 ? (long long)F * d : 0, d, gather};
+        if (r > 0) g.seg[ns++] = GemmSeg{tg, tu, w.lg, w.lu, (long long)F * r, r, 0};
+        g.nseg = ns; g.N = F; g.C = h;
+        if ((rc = run_gemm(s, g, true, st)) != MOE_OK) return rc;
+    }
+    if (r > 0) {  // td = h R_d^T   [P, r]
+        GemmArgs g = fresh();
+        g.nseg = 1; g.N = r; g.C = td;
+        g.seg[0] = GemmSeg{h, h, w.rd, w.rd, (long long)r * F, F, 0};
+        if ((rc = run_gemm(s, g, false, st)) != MOE_OK) return rc;
+    }
+    {  // y_perm = M_down h   [P, d]
+        GemmArgs g = fresh();
+        int ns = 0;
+        if (base) g.seg[ns++] = GemmSeg{h, h, w.w_down, w.w_down, r == 0 ? (long long)d * F : 0, F, 0};
+        if (r > 0) g.seg[ns++] = GemmSeg{td, td, w.ld, w.ld, (long long)d * r, r, 0};
+        g.nseg = ns; g.N = d; g.C = y_perm;
+        if ((rc = run_gemm(s, g, false, st)) != MOE_OK) return rc;
+    }
+    return MOE_OK;
+}
+
+}  // namespace moe

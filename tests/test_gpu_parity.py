@@ -1,0 +1,374 @@
+"""GPU parity: every C-ABI entry point against the CPU oracle, element by element, on the
+same seeded inputs.  Integer outputs (expert indices, offsets, permutations) must be
+bit-exact; fp32 outputs within 1e-4 relative, bf16 outputs within 2e-2 relative
+(per-tensor max-abs and L2 relative error, whichever is larger).
+
+Routing on random inputs: the GPU sums logits in fp32, the oracle in fp64, so a token
+whose k-th and (k+1)-th logits are closer than the fp32 rounding bound of the dot product
+is "ambiguous"; indices must match exactly on every other token, and on ambiguous ones
+the GPU's choice must still be admissible.  Tie-break tests use inputs whose fp32 dot
+products are exact in any order, so equality there is genuinely bit-exact.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2503_00245_amd as pkg
+import workloads as wl
+from tests.helpers import (ambiguous_tokens, bits_of, rel_err, stored_f64, to_device, to_f64,
+                           weights_to_device)
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+DT = {"f32": pkg.MOE_F32, "bf16": pkg.MOE_BF16}
+
+
+@pytest.fixture(scope="module")
+def dev():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    pkg.lib()  # fail loudly if the HIP library is not built
+    return torch.device("cuda:0")
+
+
+def _cfg(name="t", d=128, F=256, E=4, k=2, dtype="bf16", seed=1, r=0, base=False, std=0.02):
+    return wl.LayerConfig(name, d, F, E, k, dtype, seed, rank=r, shared_base=base,
+                          weight_std=std, wd_product_std=std if not base else std / 4)
+
+
+def _check_routing(oracle, x_np, w_np, k, idx_gpu, gate_gpu, probs_gpu=None):
+    """Bit-exact indices off the ambiguous set; gates/probs to fp32 accuracy. Returns mask of
+    tokens whose routing equals the oracle's."""
+    idx, gate, probs, logits = oracle.route(x_np, w_np["router_w"], w_np["router_b"], k)
+    amb = ambiguous_tokens(logits, x_np, w_np["router_w"], k)
+    same = np.all(idx_gpu == idx, axis=1)
+    assert np.all(same[~amb]), f"routing differs on {int((~same & ~amb).sum())} unambiguous tokens"
+    # an ambiguous token may pick differently, but only experts within the rounding band
+    for t in np.flatnonzero(~same):
+        kth = np.sort(logits[t])[::-1][k - 1]
+        assert len(set(idx_gpu[t])) == k
+        assert np.all(logits[t, idx_gpu[t]] >= kth - 1e-4), "inadmissible choice on ambiguous token"
+    assert amb.sum() <= max(2, x_np.shape[0] // 200), "too many ambiguous tokens for this recipe"
+    assert np.allclose(gate_gpu[same], gate[same], rtol=2e-5, atol=1e-7)
+    assert np.allclose(gate_gpu.sum(1), 1.0, atol=1e-6)
+    if probs_gpu is not None:
+        assert np.allclose(probs_gpu, probs, rtol=2e-5, atol=1e-8)
+    return same, idx, gate
+
+
+def _route_gpu(dev, x_t, w_t, E, k, act, want_probs=True):
+    T, d = x_t.shape
+    shape = pkg.make_shape(T, d, 8, E, k, 0, act)
+    idx = torch.full((T, k), -7, dtype=torch.int32, device=dev)
+    gate = torch.full((T, k), -7.0, dtype=torch.float32, device=dev)
+    probs = torch.full((T, E), -7.0, dtype=torch.float32, device=dev) if want_probs else None
+    pkg.moe_route(shape, x_t, w_t["router_w"], w_t["router_b"], idx, gate, probs)
+    torch.cuda.synchronize()
+    return idx.cpu().numpy(), gate.cpu().numpy().astype(np.float64), \
+        None if probs is None else probs.cpu().numpy().astype(np.float64)
+
+
+# ------------------------------------------------------------------------------- moe_route
+
+@pytest.mark.parametrize("T,d,E,k,dtype,bias", [
+    (32, 128, 4, 2, "f32", False),      # tiny config
+    (77, 1024, 8, 2, "bf16", False),    # wearables width, ragged token count
+    (300, 2048, 8, 2, "bf16", True),    # phone width with a router bias
+    (1, 2048, 8, 2, "bf16", True),      # single-token decode
+    (65, 256, 64, 8, "bf16", True),     # one expert per lane
+    (33, 264, 5, 1, "f32", False),      # k = 1, d not a multiple of the wave stride
+    (40, 512, 6, 6, "bf16", False),     # k = E
+])
+def test_route_matches_oracle(dev, oracle, T, d, E, k, dtype, bias):
+    cfg = _cfg(d=d, E=E, k=k, dtype=dtype, seed=300 + T)
+    w_np = wl.make_layer_weights(cfg, with_bias=False)
+    if bias:
+        w_np["router_b"] = wl.normal_tensor(cfg.seed, 99, (E,), 0.5, "f32")
+    x_np = wl.make_inputs(cfg, T)
+    w_t = weights_to_device({"router_w": w_np["router_w"], "router_b": w_np["router_b"]}, dev)
+    idx, gate, probs = _route_gpu(dev, to_device(x_np, dev), w_t, E, k, DT[dtype])
+    _check_routing(oracle, x_np, w_np, k, idx, gate, probs)
+    if k == 1:
+        assert np.all(gate == 1.0)
+
+
+def test_route_tie_break_is_lowest_index_bit_exact(dev, oracle):
+    # entries in {-1, -.5, 0, .5, 1} and a 0/1 router: every partial sum is exact in fp32
+    rng = np.random.default_rng(5)
+    E, d, T, k = 8, 64, 512, 3
+    x = (rng.integers(-2, 3, size=(T, d)) * 0.5).astype(np.float32)
+    rw = np.zeros((E, d), np.float32)
+    for e in range(E):
+        rw[e, rng.choice(d, size=4, replace=False)] = 1.0
+    rw[5] = rw[2]          # duplicated router rows: permanent ties between experts 2 and 5
+    rw[7] = rw[0]
+    w_np = {"router_w": rw, "router_b": None}
+    for dtype in ("f32", "bf16"):
+        x_np = x if dtype == "f32" else wl.f32_to_bf16_bits(x)
+        idx, gate, _ = _route_gpu(dev, to_device(x_np, dev), weights_to_device(w_np, dev), E, k,
+                                  DT[dtype])
+        ref_idx, ref_gate, _, logits = oracle.route(x_np, rw, None, k)
+        assert np.array_equal(idx, ref_idx)
+        assert np.allclose(gate, ref_gate, rtol=1e-5)
+        assert (np.sort(logits, 1)[:, -k] == np.sort(logits, 1)[:, -k - 1]).sum() > 20  # ties at the cut
+    # all-zero router: every logit equal -> experts 0..k-1, gates exactly 1/k when k is a power of 2
+    z = {"router_w": np.zeros((E, d), np.float32), "router_b": None}
+    idx, gate, probs = _route_gpu(dev, to_device(x, dev), weights_to_device(z, dev), E, 2, pkg.MOE_F32)
+    assert np.array_equal(idx, np.tile(np.arange(2, dtype=np.int32), (T, 1)))
+    assert np.all(gate == 0.5) and np.all(probs == 0.125)
+
+
+# ------------------------------------------------------------------------------- moe_permute
+
+@pytest.mark.parametrize("T,k,E", [(1, 1, 1), (1, 2, 8), (37, 2, 4), (512, 2, 8), (2048, 2, 8),
+                                   (4096, 2, 8), (4097, 2, 8), (1000, 8, 64), (50000, 3, 7)])
+def test_permute_matches_oracle_bit_exact(dev, oracle, T, k, E):
+    rng = np.random.default_rng(T * 31 + E)
+    # k distinct experts per token, skewed so some experts are empty or tiny
+    scores = rng.standard_normal((T, E)) + np.linspace(2, -2, E)
+    if E > 2:
+        scores[:, 1] = -100  # expert 1 never chosen
+    keys = np.argsort(-scores, axis=1)[:, :k].astype(np.int32)
+    d = 64
+    x_np = wl.normal_tensor(T, 1, (T, d), 1.0, "bf16")
+    shape = pkg.make_shape(T, d, 64, E, k, 0, pkg.MOE_BF16)
+    P = T * k
+    off = torch.full((E + 1,), -1, dtype=torch.int32, device=dev)
+    perm = torch.full((P,), -1, dtype=torch.int32, device=dev)
+    inv = torch.full((P,), -1, dtype=torch.int32, device=dev)
+    x_t = to_device(x_np, dev)
+    xp = torch.zeros((P, d), dtype=torch.bfloat16, device=dev)
+    ws = pkg.alloc_workspace(shape, dev)
+    pkg.moe_permute(shape, to_device(keys, dev), off, perm, inv, x_t, xp, ws)
+    torch.cuda.synchronize()
+    r_off, r_perm, r_inv = oracle.permute(keys, E)
+    assert np.array_equal(off.cpu().numpy(), r_off)
+    assert np.array_equal(perm.cpu().numpy(), r_perm)
+    assert np.array_equal(inv.cpu().numpy(), r_inv)
+    assert np.array_equal(bits_of(xp), x_np[r_perm // k])
+    # unpermute(permute(x)) is the identity on the payload
+    assert np.array_equal(bits_of(xp)[r_inv].reshape(T, k, d)[:, 0], x_np)
+
+
+# ------------------------------------------------------------------------------- moe_expert_ffn
+
+def _ffn_case(dev, oracle, cfg, offsets, tol):
+    w_np = wl.make_layer_weights(cfg, with_bias=False)
+    P = int(offsets[-1])
+    xp_np = wl.normal_tensor(cfg.seed, 77, (P, cfg.d_model), 1.0, cfg.act_dtype)
+    w_t = weights_to_device(w_np, dev)
+    # the staged call sees P rows as P "tokens" with k = 1
+    shape = pkg.shape_for(w_t, P, 1, DT[cfg.act_dtype])
+    ws = pkg.alloc_workspace(shape, dev)
+    xp = to_device(xp_np, dev)
+    yp = torch.full_like(xp, float("nan"))
+    pkg.moe_expert_ffn(shape, pkg.make_weights(w_t), xp, to_device(offsets, dev), yp, ws)
+    torch.cuda.synchronize()
+    ref = oracle.expert_ffn(w_np, xp_np, offsets)
+    got = to_f64(yp)
+    assert np.all(np.isfinite(got))
+    err = rel_err(got, ref)
+    assert err < tol, f"relative error {err:.3e} >= {tol}"
+    return err
+
+
+def test_expert_ffn_tiny_fp32(dev, oracle):
+    cfg = _cfg(d=128, F=256, E=4, dtype="f32", seed=401, std=0.05)
+    _ffn_case(dev, oracle, cfg, np.array([0, 20, 20, 49, 64], np.int32), TOL["f32"])
+
+
+@pytest.mark.parametrize("d,F,offsets", [
+    (256, 384, [0, 130, 130, 257, 300]),          # several m-tiles, an empty expert, ragged tails
+    (200, 328, [0, 1, 3, 70, 71]),                # K and N not multiples of the tile, tiny groups
+    (1024, 2816, [0, 64, 200, 200, 333, 333, 400, 401, 520]),  # wearables widths, 8 experts
+])
+def test_expert_ffn_dense_bf16(dev, oracle, d, F, offsets):
+    cfg = _cfg(d=d, F=F, E=len(offsets) - 1, dtype="bf16", seed=402 + d, std=0.05)
+    _ffn_case(dev, oracle, cfg, np.array(offsets, np.int32), TOL["bf16"])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("base", [False, True])
+def test_expert_ffn_weight_decomposed(dev, oracle, dtype, base):
+    cfg = _cfg(d=256, F=448, E=4, dtype=dtype, seed=410, r=(40 if base else 128), base=base, std=0.05)
+    _ffn_case(dev, oracle, cfg, np.array([0, 150, 150, 161, 300], np.int32), TOL[dtype])
+
+
+# ------------------------------------------------------------------------------- moe_combine
+
+@pytest.mark.parametrize("dtype,residual", [("f32", False), ("bf16", True), ("bf16", False)])
+def test_combine_matches_oracle(dev, oracle, dtype, residual):
+    T, k, d, E = 75, 3, 264, 6
+    rng = np.random.default_rng(9)
+    keys = np.argsort(rng.standard_normal((T, E)), axis=1)[:, :k].astype(np.int32)
+    _, _, inv = oracle.permute(keys, E)
+    yp_np = wl.normal_tensor(9, 1, (T * k, d), 1.0, dtype)
+    res_np = wl.normal_tensor(9, 2, (T, d), 1.0, dtype) if residual else None
+    g = rng.random((T, k)).astype(np.float32)
+    g /= g.sum(1, keepdims=True)
+    shape = pkg.make_shape(T, d, 64, E, k, 0, DT[dtype])
+    y = torch.empty((T, d), dtype=torch.float32 if dtype == "f32" else torch.bfloat16, device=dev)
+    pkg.moe_combine(shape, to_device(yp_np, dev), to_device(inv, dev), to_device(g, dev),
+                    to_device(res_np, dev), y)
+    torch.cuda.synchronize()
+    ref = oracle.combine(stored_f64(yp_np), inv, g.astype(np.float64), residual=res_np)
+    assert rel_err(to_f64(y), ref) < (1e-6 if dtype == "f32" else 5e-3)
+
+
+# ------------------------------------------------------------------------------- moe_forward
+
+def _forward_gpu(dev, w_t, x_t, k, act, residual=False):
+    T = x_t.shape[0]
+    shape = pkg.shape_for(w_t, T, k, act, residual=residual)
+    ws = pkg.alloc_workspace(shape, dev)
+    y = torch.full_like(x_t, float("nan"))
+    idx = torch.full((T, k), -1, dtype=torch.int32, device=dev)
+    gate = torch.zeros((T, k), dtype=torch.float32, device=dev)
+    pkg.moe_forward(shape, pkg.make_weights(w_t), x_t, y, idx, gate, ws)
+    torch.cuda.synchronize()
+    return y, idx.cpu().numpy(), gate.cpu().numpy().astype(np.float64)
+
+
+def _forward_case(dev, oracle, cfg, T, w_np=None, w_t=None, sample=None, residual=False):
+    """moe_forward vs the oracle.  sample: compare y only on that many seeded tokens (routing
+    is always compared on all of them)."""
+    if w_np is None:
+        w_np = wl.make_layer_weights(cfg)
+    if w_t is None:
+        w_t = weights_to_device(w_np, dev)
+    x_np = wl.make_inputs(cfg, T)
+    y, idx, gate = _forward_gpu(dev, w_t, to_device(x_np, dev), cfg.top_k, DT[cfg.act_dtype], residual)
+    same, _, _ = _check_routing(oracle, x_np, w_np, cfg.top_k, idx, gate)
+    got = to_f64(y)
+    assert np.all(np.isfinite(got))
+    toks = np.arange(T)
+    if sample is not None and sample < T:
+        toks = np.sort(np.random.default_rng(cfg.seed).choice(T, size=sample, replace=False))
+    toks = toks[same[toks]]
+    ref, ridx, _ = oracle.forward(w_np, np.ascontiguousarray(x_np[toks]), cfg.top_k, residual=residual)
+    assert np.array_equal(ridx, idx[toks])
+    err = rel_err(got[toks], ref)
+    tol = TOL[cfg.act_dtype]
+    assert err < tol, f"{cfg.name} T={T}: relative error {err:.3e} >= {tol}"
+    return err
+
+
+def test_forward_tiny_fp32_config(dev, oracle):
+    cfg = wl.CONFIGS["tiny"]
+    _forward_case(dev, oracle, cfg, 32)
+    _forward_case(dev, oracle, cfg, 1)
+    _forward_case(dev, oracle, cfg, 5, residual=True)
+
+
+@pytest.mark.parametrize("T", [1, 2, 3, 130, 512])
+def test_forward_wearables_config(dev, oracle, T):
+    _forward_case(dev, oracle, wl.CONFIGS["wearables"], T, sample=96)
+
+
+@pytest.fixture(scope="module")
+def phone(dev):
+    cfg = wl.CONFIGS["phone"]
+    w_np = wl.make_layer_weights(cfg)
+    return cfg, w_np, weights_to_device(w_np, dev)
+
+
+def test_forward_phone_config_decode_and_prefill(dev, oracle, phone):
+    cfg, w_np, w_t = phone
+    _forward_case(dev, oracle, cfg, 1, w_np, w_t)
+    _forward_case(dev, oracle, cfg, 2048, w_np, w_t, sample=48)
+    # the stored router bias must realise the Zipf(1.1) expert loads it was calibrated for
+    x_np = wl.make_inputs(cfg, 2048)
+    idx, _, _, _ = oracle.route(x_np, w_np["router_w"], w_np["router_b"], cfg.top_k)
+    share = np.bincount(idx.reshape(-1), minlength=8) / idx.size
+    assert np.abs(share - wl.zipf_target_shares(8, 1.1)).max() < 0.01
+
+
+@pytest.mark.parametrize("name", ["phone_wd", "phone_wd_base"])
+def test_forward_phone_weight_decomposed_configs(dev, oracle, name):
+    cfg = wl.CONFIGS[name]
+    w_np = wl.make_layer_weights(cfg)
+    w_t = weights_to_device(w_np, dev)
+    _forward_case(dev, oracle, cfg, 1, w_np, w_t)
+    _forward_case(dev, oracle, cfg, 2048, w_np, w_t, sample=32)
+
+
+def test_forward_small_shapes_all_expert_kinds(dev, oracle):
+    for dtype in ("f32", "bf16"):
+        for r, base in ((0, False), (64, False), (24, True)):
+            cfg = _cfg(name=f"s{r}{base}", d=192, F=328, E=5, k=3, dtype=dtype, seed=500 + r,
+                       r=r, base=base, std=0.05)
+            for T in (1, 7, 150):
+                _forward_case(dev, oracle, cfg, T, residual=(T == 7))
+
+
+def test_forward_is_deterministic_and_matches_the_staged_calls(dev, oracle):
+    cfg = wl.shrink(wl.CONFIGS["wearables"], d_model=512, d_ff=1024)
+    w_np = wl.make_layer_weights(cfg)
+    w_t = weights_to_device(w_np, dev)
+    T, k = 200, cfg.top_k
+    x_t = to_device(wl.make_inputs(cfg, T), dev)
+    y1, idx1, gate1 = _forward_gpu(dev, w_t, x_t, k, pkg.MOE_BF16)
+    y2, idx2, gate2 = _forward_gpu(dev, w_t, x_t, k, pkg.MOE_BF16)
+    assert torch.equal(y1, y2) and np.array_equal(idx1, idx2) and np.array_equal(gate1, gate2)
+    # staged pipeline through the same ABI
+    shape = pkg.shape_for(w_t, T, k, pkg.MOE_BF16)
+    ws = pkg.alloc_workspace(shape, dev)
+    P = T * k
+    idx = torch.empty((T, k), dtype=torch.int32, device=dev)
+    gate = torch.empty((T, k), dtype=torch.float32, device=dev)
+    pkg.moe_route(shape, x_t, w_t["router_w"], None, idx, gate, None)
+    off = torch.empty(cfg.n_experts + 1, dtype=torch.int32, device=dev)
+    perm = torch.empty(P, dtype=torch.int32, device=dev)
+    inv = torch.empty(P, dtype=torch.int32, device=dev)
+    xp = torch.empty((P, cfg.d_model), dtype=torch.bfloat16, device=dev)
+    pkg.moe_permute(shape, idx, off, perm, inv, x_t, xp, ws)
+    yp = torch.empty_like(xp)
+    ffn_shape = pkg.shape_for(w_t, P, 1, pkg.MOE_BF16)
+    pkg.moe_expert_ffn(ffn_shape, pkg.make_weights(w_t), xp, off, yp, pkg.alloc_workspace(ffn_shape, dev))
+    y3 = torch.empty_like(x_t)
+    pkg.moe_combine(shape, yp, inv, gate, None, y3)
+    torch.cuda.synchronize()
+    assert np.array_equal(idx.cpu().numpy(), idx1)          # routing bit-identical
+    assert np.array_equal(gate.cpu().numpy().astype(np.float64), gate1)
+    assert torch.equal(y3, y1)                               # same kernels, same bits
+
+
+# ------------------------------------------------------------------------------- moe_stack_forward
+
+def _stack_case(dev, oracle, cfg, n_layers, T):
+    layers_np = wl.make_stack_weights(cfg, n_layers)
+    layers_t = [weights_to_device(w, dev) for w in layers_np]
+    x_np = wl.make_inputs(cfg, T)
+    act = DT[cfg.act_dtype]
+    shape = pkg.shape_for(layers_t[0], T, cfg.top_k, act)
+    ws = pkg.alloc_workspace(shape, dev)
+    x_t = to_device(x_np, dev)
+    y = torch.empty_like(x_t)
+    trace = torch.full((n_layers, T, cfg.top_k), -1, dtype=torch.int32, device=dev)
+    pkg.moe_stack_forward(shape, [pkg.make_weights(w) for w in layers_t], x_t, y, trace, ws)
+    torch.cuda.synchronize()
+    y_ref, trace_ref, xs = oracle.stack_forward(layers_np, x_np, cfg.top_k)
+    trace = trace.cpu().numpy()
+    # free-running: compare the final residual on tokens whose routing never flipped
+    clean = np.all(trace == trace_ref, axis=(0, 2))
+    assert clean.mean() > 0.9, "too many routing flips for near-tie noise"
+    err = rel_err(to_f64(y)[clean], y_ref[clean])
+    assert err < TOL[cfg.act_dtype], f"stack error {err:.3e}"
+    # teacher-forced: each GPU layer fed the oracle's (storage-rounded) input of that layer
+    for l in range(n_layers):
+        xin = xs[l].astype(np.float32)
+        xin = xin if cfg.act_dtype == "f32" else wl.f32_to_bf16_bits(xin)
+        yl, idx, gate = _forward_gpu(dev, layers_t[l], to_device(xin, dev), cfg.top_k, act, residual=True)
+        same, _, _ = _check_routing(oracle, xin, layers_np[l], cfg.top_k, idx, gate)
+        ref, _, _ = oracle.forward(layers_np[l], xin, cfg.top_k, residual=True)
+        assert rel_err(to_f64(yl)[same], ref[same]) < TOL[cfg.act_dtype]
+
+
+def test_stack_small(dev, oracle):
+    cfg = wl.shrink(wl.CONFIGS["phone_stack"], d_model=256, d_ff=512, weight_std=0.05)
+    _stack_case(dev, oracle, cfg, 5, 1)
+    _stack_case(dev, oracle, cfg, 4, 40)
+
+
+def test_stack_phone_width_decode(dev, oracle):
+    _stack_case(dev, oracle, wl.CONFIGS["phone_stack"], 3, 1)
