@@ -1,0 +1,264 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE feed-forward layer on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+A step is one pass of the whole layer (route -> dispatch -> expert FFN -> combine, the
+moe_forward entry point) over one batch of seeded synthetic tokens that is already
+resident in HBM.  W untimed steps, then exactly K timed steps bracketed by device
+synchronisation; one JSON line is printed.
+
+  value      tokens/s of the whole layer over the K timed steps
+  roofline   for the dominant kernel of the workload: algorithmic flops (prefill, MFMA
+             bound) or bytes (decode, HBM bound) per launch divided by that kernel's
+             average duration, measured with HIP events on the launch stream in a
+             second pass of K steps through moe_forward_timed (same kernels, same
+             inputs; the events are kept out of the tokens/s pass)
+  stages     average milliseconds of every stage kernel from that second pass
+  cpu_baseline  the CPU oracle, as it stands, timed on this host on a bounded sample
+
+Workloads (shapes of the benchmark configurations):
+  phone_prefill (default)  d 2048, F 5632, E 8, k 2, bf16, T = 2048, Zipf(1.1) expert loads
+  phone_decode             same layer, T = 1, fresh token per step, cold weights
+  wearables_prefill        d 1024, F 2816, T = 512      wearables_decode   T = 1
+  phone_wd_prefill / phone_wd_decode            pure L.R experts, r = 1024
+  phone_wd_base_prefill / phone_wd_base_decode  shared base + rank-64 pair
+  phone_stack_decode       24 phone-shaped layers with residual adds, T = 1, one step =
+                           one token through all 24 layers (--steps 256 = the full loop)
+Decode workloads rotate over several device copies of the layer so that consecutive
+steps never find their weights in the 256 MB last-level cache.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+
+WORKLOADS = {
+    "phone_prefill": ("phone", 2048),
+    "phone_decode": ("phone", 1),
+    "wearables_prefill": ("wearables", 512),
+    "wearables_decode": ("wearables", 1),
+    "phone_wd_prefill": ("phone_wd", 2048),
+    "phone_wd_decode": ("phone_wd", 1),
+    "phone_wd_base_prefill": ("phone_wd_base", 2048),
+    "phone_wd_base_decode": ("phone_wd_base", 1),
+    "phone_stack_decode": ("phone_stack", 1),
+}
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs (see profiles/); None until measured for that workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def layer_weight_bytes(cfg):
+    d, F, E, r = cfg.d_model, cfg.d_ff, cfg.n_experts, cfg.rank
+    dense = 3 * d * F * 2
+    fac = 3 * r * (d + F) * 2
+    if r == 0:
+        return E * dense
+    return E * fac + (dense if cfg.shared_base else 0)
+
+
+def dominant_kernel_work(cfg, T):
+    """(stage name, bound, algorithmic work per launch, unit) of the dominant kernel."""
+    d, F, k, r = cfg.d_model, cfg.d_ff, cfg.top_k, cfg.rank
+    P = T * k
+    if T == 1:
+        # single token: the gate/up product streams k experts' gate and up matrices once
+        if r == 0:
+            nbytes = k * 2 * F * d * 2
+        else:
+            nbytes = k * 2 * F * r * 2 + (2 * F * d * 2 if cfg.shared_base else 0)
+        return "gemv_gate_up_swiglu", "hbm", float(nbytes), "GB/s"
+    flops = 4.0 * P * F * (r if r else d)
+    if cfg.shared_base:
+        flops += 4.0 * P * F * d
+    return "gemm_gate_up_swiglu", "mfma", flops, "TFLOP/s"
+
+
+def layer_algorithmic(cfg, T):
+    """Whole-layer algorithmic (flops, expert-weight bytes streamed) per forward."""
+    d, F, k, r, E = cfg.d_model, cfg.d_ff, cfg.top_k, cfg.rank, cfg.n_experts
+    P = T * k
+    if r == 0:
+        flops = 6.0 * P * d * F
+        per_expert = 3 * d * F * 2
+        nbytes = min(P, E) * per_expert if T == 1 else E * per_expert
+    else:
+        flops = 6.0 * P * r * (d + F) + (6.0 * P * d * F if cfg.shared_base else 0)
+        per_expert = 3 * r * (d + F) * 2
+        nbytes = (min(P, E) if T == 1 else E) * per_expert + (3 * d * F * 2 if cfg.shared_base else 0)
+    return flops, float(nbytes)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="phone_prefill", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0,
+                    help="target wall time of the CPU oracle sample")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              f"--gpus {args.gpus} is not supported. Re-run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2503_00245_amd as pkg
+    import workloads as wl
+
+    pkg.lib()  # fail loudly if the HIP library is missing
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    cfg_name, T = WORKLOADS[args.workload]
+    cfg = wl.CONFIGS[cfg_name]
+    decode = T == 1
+    stack = cfg.n_layers > 1
+    steps = args.steps if args.steps is not None else (256 if stack else (2000 if decode else 200))
+    warmup = args.warmup if args.warmup is not None else (8 if stack else (50 if decode else 10))
+
+    def dev_t(a):
+        if a is None:
+            return None
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).to(dev)
+        return torch.from_numpy(a).to(dev)
+
+    # ---- inputs: generated on the host from the seed, then resident in HBM ---------------
+    t_gen = time.time()
+    if stack:
+        layers_np = wl.make_stack_weights(cfg, workers=8)
+    else:
+        layers_np = [wl.make_layer_weights(cfg)]
+    layers_t = [{k: dev_t(v) for k, v in w.items()} for w in layers_np]
+    n_inputs = 256 if decode else 4
+    xs_np = [wl.make_inputs(cfg, T, step=i) for i in range(n_inputs)]
+    xs = [dev_t(x) for x in xs_np]
+    # cold-cache rotation for single-layer decode: enough copies to exceed the LLC several times
+    copies = [layers_t]
+    if decode and not stack:
+        n_copies = max(2, int(np.ceil(1.5e9 / layer_weight_bytes(cfg))))
+        for _ in range(n_copies - 1):
+            copies.append([{k: (None if v is None else v.clone()) for k, v in layers_t[0].items()}])
+    gen_s = time.time() - t_gen
+
+    shape = pkg.shape_for(layers_t[0], T, cfg.top_k, pkg.MOE_BF16)
+    ws = pkg.alloc_workspace(shape, dev)
+    y = torch.empty_like(xs[0])
+    w_structs = [[pkg.make_weights(w) for w in c] for c in copies]
+
+    def step(i):
+        ws_i = w_structs[i % len(w_structs)]
+        if stack:
+            pkg.moe_stack_forward(shape, ws_i, xs[i % n_inputs], y, None, ws)
+        else:
+            pkg.moe_forward(shape, ws_i[0], xs[i % n_inputs], y, None, None, ws)
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(warmup + i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / steps * 1e3
+    tokens_per_s = T * steps / elapsed
+
+    # ---- second pass: per-stage durations from HIP events on the launch stream ------------
+    stage_sum = {}
+    order = []
+    n_timed = min(steps, 200) if not stack else min(steps, 8)
+    single = pkg.shape_for(layers_t[0], T, cfg.top_k, pkg.MOE_BF16, residual=stack)
+    for i in range(n_timed):
+        ws_i = w_structs[i % len(w_structs)]
+        for l, wst in enumerate(ws_i):
+            for name, ms in pkg.moe_forward_timed(single, wst, xs[(i + l) % n_inputs], y, ws):
+                if name not in stage_sum:
+                    stage_sum[name] = 0.0
+                    order.append(name)
+                stage_sum[name] += ms
+    n_launch = n_timed * len(w_structs[0])
+    stages = {n: stage_sum[n] / n_launch for n in order}
+
+    kname, bound, work, unit = dominant_kernel_work(cfg, T)
+    kms = stages[kname]
+    if bound == "hbm":
+        achieved = work / (kms * 1e-3) / 1e9
+        peak = HBM_PEAK_GBS
+    else:
+        achieved = work / (kms * 1e-3) / 1e12
+        peak = MFMA_BF16_PEAK_TFLOPS
+    roofline = {"bound": bound, "achieved": round(achieved, 2), "peak": peak, "unit": unit,
+                "frac": round(achieved / peak, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
+                "kernel": kname, "kernel_ms": round(kms, 5), "algorithmic_per_launch": work}
+    flops, wbytes = layer_algorithmic(cfg, T)
+    n_l = cfg.n_layers
+    layer = {"mfma_frac_of_peak": round(flops * n_l / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+             "hbm_frac_of_peak": round(wbytes * n_l / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+             "algorithmic_flops": flops * n_l, "algorithmic_weight_bytes": wbytes * n_l,
+             "sum_of_stage_ms": round(sum(stages.values()), 5)}
+
+    # ---- CPU oracle baseline on a bounded sample of the same workload -------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import moe_oracle
+        k = cfg.top_k
+
+        def run_oracle(n_tok):
+            t1 = time.perf_counter()
+            if stack:
+                for i in range(n_tok):
+                    moe_oracle.stack_forward(layers_np, xs_np[i % n_inputs], k)
+            elif decode:
+                for i in range(n_tok):
+                    moe_oracle.forward(layers_np[0], xs_np[i % n_inputs], k)
+            else:
+                moe_oracle.forward(layers_np[0], np.ascontiguousarray(xs_np[0][:n_tok]), k)
+            return time.perf_counter() - t1
+
+        probe_n = 1 if (decode or stack) else min(T, 2 * moe_oracle.num_threads())
+        probe = run_oracle(probe_n)
+        n_sample = int(max(probe_n, min(T if not decode else 4096,
+                                        probe_n * args.cpu_seconds / max(probe, 1e-6))))
+        if stack:
+            n_sample = max(1, min(n_sample, 4))
+        if not (decode or stack):
+            n_sample = max(probe_n, n_sample // probe_n * probe_n)
+        took = run_oracle(n_sample)
+        cpu = {"value": round(n_sample / took, 3), "unit": "tokens/s",
+               "cores": moe_oracle.num_threads(), "kind": "oracle",
+               "sample": f"{n_sample} token(s) of the {args.workload} workload through the fp64 C "
+                         f"oracle in {took:.2f} s"}
+
+    out = {
+        "metric": "moe_layer_tokens_per_s", "value": round(tokens_per_s, 2), "unit": "tokens/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "d_model": cfg.d_model, "d_ff": cfg.d_ff,
+                   "n_experts": cfg.n_experts, "top_k": cfg.top_k, "rank": cfg.rank,
+                   "shared_base": cfg.shared_base, "n_layers": cfg.n_layers, "tokens_per_step": T,
+                   "zipf_router_bias": bool(cfg.zipf), "weight_copies_rotated": len(copies)},
+        "roofline": roofline, "cpu_baseline": cpu, "stages_ms": {k: round(v, 5) for k, v in stages.items()},
+        "layer": layer, "input_generation_s": round(gen_s, 1),
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -168,6 +168,20 @@ MOE_API int moe_stack_forward(const moe_shape* shape, const moe_weights* layers,
                       const void* x, void* y, int32_t* topk_trace, void* workspace,
                       size_t workspace_bytes, void* stream);
 
+/*
+ * Measurement aid (not an operation of the paper): does exactly what moe_forward does, with
+ * a hipEventRecord on `stream` before the first and after every stage kernel, then
+ * SYNCHRONISES the stream and reports each stage's elapsed time.  Unlike the other entry
+ * points it creates and destroys events and blocks the host.
+ *   stage_ms    [MOE_MAX_STAGES] host floats, out: milliseconds per stage
+ *   stage_names [MOE_MAX_STAGES] host, out or NULL: static strings naming each stage
+ *   n_stages    host, out: how many stages ran
+ */
+#define MOE_MAX_STAGES 8
+MOE_API int moe_forward_timed(const moe_shape* shape, const moe_weights* weights, const void* x,
+                              void* y, void* workspace, size_t workspace_bytes, void* stream,
+                              float* stage_ms, const char** stage_names, int32_t* n_stages);
+
 /* Bytes of workspace that any entry point above needs for this shape (0 if invalid). */
 MOE_API size_t moe_workspace_bytes(const moe_shape* shape);
 

@@ -20,7 +20,7 @@ FLAG_SHARED_BASE, FLAG_RESIDUAL = 1, 2
 WEIGHT_FIELDS = ("router_w", "router_b", "w_gate", "w_up", "w_down",
                  "rg", "ru", "rd", "lg", "lu", "ld")
 EXPORTS = ("moe_route", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_forward",
-           "moe_stack_forward", "moe_workspace_bytes", "moe_status_string")
+           "moe_stack_forward", "moe_forward_timed", "moe_workspace_bytes", "moe_status_string")
 
 
 class MoeShape(C.Structure):
@@ -62,8 +62,10 @@ def lib() -> C.CDLL:
         L.moe_combine.argtypes = [sp, vp, vp, vp, vp, vp, vp]
         L.moe_forward.argtypes = [sp, wp, vp, vp, vp, vp, vp, sz, vp]
         L.moe_stack_forward.argtypes = [sp, wp, C.c_int32, vp, vp, vp, vp, sz, vp]
+        L.moe_forward_timed.argtypes = [sp, wp, vp, vp, vp, sz, vp, C.POINTER(C.c_float),
+                                        C.POINTER(C.c_char_p), C.POINTER(C.c_int32)]
         for fn in ("moe_route", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_forward",
-                   "moe_stack_forward"):
+                   "moe_stack_forward", "moe_forward_timed"):
             getattr(L, fn).restype = C.c_int
         _lib = L
     return _lib
@@ -176,3 +178,17 @@ def moe_stack_forward(shape: MoeShape, layers: Sequence[MoeWeights], x, y, topk_
     _check("moe_stack_forward", lib().moe_stack_forward(
         C.byref(shape), arr, len(layers), _ptr(x), _ptr(y), _ptr(topk_trace), _ptr(workspace),
         0 if workspace is None else workspace.numel(), _stream(y.device)))
+
+
+MAX_STAGES = 8
+
+
+def moe_forward_timed(shape: MoeShape, weights: MoeWeights, x, y, workspace):
+    """One forward with per-stage HIP-event timing; returns [(stage name, milliseconds)]."""
+    ms = (C.c_float * MAX_STAGES)()
+    names = (C.c_char_p * MAX_STAGES)()
+    n = C.c_int32(0)
+    _check("moe_forward_timed", lib().moe_forward_timed(
+        C.byref(shape), C.byref(weights), _ptr(x), _ptr(y), _ptr(workspace), workspace.numel(),
+        _stream(y.device), ms, names, C.byref(n)))
+    return [(names[i].decode(), float(ms[i])) for i in range(n.value)]

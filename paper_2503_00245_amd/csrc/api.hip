@@ -66,25 +66,31 @@ static Workspace carve(const moe_shape& s) {
 }
 
 static int forward_impl(const moe_shape& s, const moe_weights& w, const void* x, void* y,
-                        int32_t* topk_idx, float* topk_gate, char* wsp, hipStream_t st) {
+                        int32_t* topk_idx, float* topk_gate, char* wsp, hipStream_t st,
+                        StageTimer* timer = nullptr) {
     const Workspace ws = carve(s);
     int32_t* idx = topk_idx ? topk_idx : reinterpret_cast<int32_t*>(wsp + ws.topk_idx);
     float* gate = topk_gate ? topk_gate : reinterpret_cast<float*>(wsp + ws.topk_gate);
     int rc = launch_route(s, x, w.router_w, w.router_b, idx, gate, nullptr, st);
     if (rc != MOE_OK) return rc;
+    stage_mark(timer, "route");
     if (decode_supported(s))
-        return launch_decode_ffn(s, w, x, idx, gate, y, wsp + ws.decode_scratch, st);
+        return launch_decode_ffn(s, w, x, idx, gate, y, wsp + ws.decode_scratch, st, timer);
     const int P = s.n_tokens * s.top_k;
     int32_t* offsets = reinterpret_cast<int32_t*>(wsp + ws.offsets);
     int32_t* perm = reinterpret_cast<int32_t*>(wsp + ws.perm);
     int32_t* inv_perm = reinterpret_cast<int32_t*>(wsp + ws.inv_perm);
     rc = launch_permute(P, s.n_experts, idx, offsets, perm, inv_perm, wsp + ws.sort_scratch, st);
     if (rc != MOE_OK) return rc;
+    stage_mark(timer, "permute");
     // the gather of token rows into expert order is fused into the first GEMM's A loads
-    rc = launch_expert_ffn(s, w, x, perm, s.top_k, offsets, wsp + ws.y_perm, wsp + ws.ffn_scratch, st);
+    rc = launch_expert_ffn(s, w, x, perm, s.top_k, offsets, wsp + ws.y_perm, wsp + ws.ffn_scratch, st,
+                           timer);
     if (rc != MOE_OK) return rc;
-    return launch_combine(s, wsp + ws.y_perm, inv_perm, gate,
-                          (s.flags & MOE_FLAG_RESIDUAL) ? x : nullptr, y, st);
+    rc = launch_combine(s, wsp + ws.y_perm, inv_perm, gate,
+                        (s.flags & MOE_FLAG_RESIDUAL) ? x : nullptr, y, st);
+    stage_mark(timer, "combine");
+    return rc;
 }
 
 }  // namespace moe
@@ -175,6 +181,38 @@ int moe_forward(const moe_shape* shape, const moe_weights* weights, const void* 
         return MOE_ERR_WORKSPACE;
     return forward_impl(*shape, *weights, x, y, topk_idx, topk_gate, static_cast<char*>(workspace),
                         as_stream(stream));
+}
+
+int moe_forward_timed(const moe_shape* shape, const moe_weights* weights, const void* x, void* y,
+                      void* workspace, size_t workspace_bytes, void* stream, float* stage_ms,
+                      const char** stage_names, int32_t* n_stages) {
+    if (!stage_ms || !n_stages) return MOE_ERR_INVALID;
+    *n_stages = 0;
+    int rc = validate_shape(shape);
+    if (rc != MOE_OK) return rc;
+    if ((rc = validate_weights(*shape, weights, true)) != MOE_OK) return rc;
+    if (shape->n_tokens == 0) return MOE_OK;
+    if (!x || !y || x == y || !aligned16(x) || !aligned16(y)) return MOE_ERR_INVALID;
+    if (!workspace || !aligned16(workspace) || workspace_bytes < carve(*shape).total)
+        return MOE_ERR_WORKSPACE;
+    StageTimer timer{};
+    timer.st = as_stream(stream);
+    for (auto& e : timer.ev)
+        if (hipEventCreate(&e) != hipSuccess) return MOE_ERR_LAUNCH;
+    (void)hipEventRecord(timer.ev[0], timer.st);
+    rc = forward_impl(*shape, *weights, x, y, nullptr, nullptr, static_cast<char*>(workspace),
+                      timer.st, &timer);
+    if (hipStreamSynchronize(timer.st) != hipSuccess && rc == MOE_OK) rc = MOE_ERR_LAUNCH;
+    if (rc == MOE_OK) {
+        for (int i = 0; i < timer.n; ++i) {
+            if (hipEventElapsedTime(&stage_ms[i], timer.ev[i], timer.ev[i + 1]) != hipSuccess)
+                rc = MOE_ERR_LAUNCH;
+            if (stage_names) stage_names[i] = timer.name[i];
+        }
+        *n_stages = timer.n;
+    }
+    for (auto& e : timer.ev) (void)hipEventDestroy(e);
+    return rc;
 }
 
 int moe_stack_forward(const moe_shape* shape, const moe_weights* layers, int32_t n_layers,

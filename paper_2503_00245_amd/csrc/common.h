@@ -57,6 +57,21 @@ inline size_t elt_size(int act_dtype) { return act_dtype == MOE_F32 ? 4 : 2; }
 
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// Optional per-stage timing (moe_forward_timed): an event before the first stage and after
+// every stage kernel, all on the launch stream.  A null timer costs nothing.
+struct StageTimer {
+    hipStream_t st;
+    hipEvent_t ev[MOE_MAX_STAGES + 1];
+    const char* name[MOE_MAX_STAGES];
+    int n;
+};
+inline void stage_mark(StageTimer* t, const char* name) {
+    if (!t || t->n >= MOE_MAX_STAGES) return;
+    t->name[t->n] = name;
+    (void)hipEventRecord(t->ev[t->n + 1], t->st);
+    t->n += 1;
+}
+
 // Shape check shared by every entry point: MOE_OK, MOE_ERR_INVALID or MOE_ERR_UNSUPPORTED.
 int validate_shape(const moe_shape* s);
 
@@ -78,12 +93,12 @@ int launch_combine(const moe_shape& s, const void* y_perm, const int32_t* inv_pe
 size_t ffn_scratch_bytes(const moe_shape& s);
 int launch_expert_ffn(const moe_shape& s, const moe_weights& w, const void* x,
                       const int32_t* a_row_map, int a_row_div, const int32_t* offsets,
-                      void* y_perm, void* scratch, hipStream_t st);
+                      void* y_perm, void* scratch, hipStream_t st, StageTimer* timer = nullptr);
 
 // Single-token layer: experts chosen on the device from topk_idx, weights streamed once.
 size_t decode_scratch_bytes(const moe_shape& s);
 int launch_decode_ffn(const moe_shape& s, const moe_weights& w, const void* x,
                       const int32_t* topk_idx, const float* topk_gate, void* y, void* scratch,
-                      hipStream_t st);
+                      hipStream_t st, StageTimer* timer = nullptr);
 
 }  // namespace moe

@@ -349,7 +349,7 @@ size_t ffn_scratch_bytes(const moe_shape& s) {
 
 int launch_expert_ffn(const moe_shape& s, const moe_weights& w, const void* x,
                       const int32_t* a_row_map, int a_row_div, const int32_t* offsets,
-                      void* y_perm, void* scratch, hipStream_t st) {
+                      void* y_perm, void* scratch, hipStream_t st, StageTimer* timer) {
     const int d = s.d_model, F = s.d_ff, r = s.rank, E = s.n_experts;
     const int P = s.n_tokens * s.top_k;
     if (P == 0) return MOE_OK;
@@ -376,10 +376,12 @@ int launch_expert_ffn(const moe_shape& s, const moe_weights& w, const void* x,
         g.nseg = 1; g.N = r; g.C = tg;
         g.seg[0] = GemmSeg{x, x, w.rg, w.rg, (long long)r * d, d, gather};
         if ((rc = run_gemm(s, g, false, st)) != MOE_OK) return rc;
+        stage_mark(timer, "gemm_rank_gate");
         g = fresh();
         g.nseg = 1; g.N = r; g.C = tu;
         g.seg[0] = GemmSeg{x, x, w.ru, w.ru, (long long)r * d, d, gather};
         if ((rc = run_gemm(s, g, false, st)) != MOE_OK) return rc;
+        stage_mark(timer, "gemm_rank_up");
     }
     {  // h = silu(M_gate x) * (M_up x)   [P, F]
         GemmArgs g = fresh();
@@ -388,12 +390,14 @@ int launch_expert_ffn(const moe_shape& s, const moe_weights& w, const void* x,
         if (r > 0) g.seg[ns++] = GemmSeg{tg, tu, w.lg, w.lu, (long long)F * r, r, 0};
         g.nseg = ns; g.N = F; g.C = h;
         if ((rc = run_gemm(s, g, true, st)) != MOE_OK) return rc;
+        stage_mark(timer, "gemm_gate_up_swiglu");
     }
     if (r > 0) {  // td = h R_d^T   [P, r]
         GemmArgs g = fresh();
         g.nseg = 1; g.N = r; g.C = td;
         g.seg[0] = GemmSeg{h, h, w.rd, w.rd, (long long)r * F, F, 0};
         if ((rc = run_gemm(s, g, false, st)) != MOE_OK) return rc;
+        stage_mark(timer, "gemm_rank_down");
     }
     {  // y_perm = M_down h   [P, d]
         GemmArgs g = fresh();
@@ -402,6 +406,7 @@ int launch_expert_ffn(const moe_shape& s, const moe_weights& w, const void* x,
         if (r > 0) g.seg[ns++] = GemmSeg{td, td, w.ld, w.ld, (long long)d * r, r, 0};
         g.nseg = ns; g.N = d; g.C = y_perm;
         if ((rc = run_gemm(s, g, false, st)) != MOE_OK) return rc;
+        stage_mark(timer, "gemm_down");
     }
     return MOE_OK;
 }

@@ -229,7 +229,7 @@ bool decode_supported(const moe_shape& s) {
 template <typename T>
 static int decode_ffn_t(const moe_shape& s, const moe_weights& w, const void* x,
                         const int32_t* idx, const float* gate, void* y, void* scratch,
-                        hipStream_t st) {
+                        hipStream_t st, StageTimer* timer) {
     const int d = s.d_model, F = s.d_ff, r = s.rank, k = s.top_k;
     const bool base = (r == 0) || (s.flags & MOE_FLAG_SHARED_BASE);
     const long long base_stride_gu = (r == 0) ? (long long)F * d : 0;  // shared base: stride 0
@@ -246,6 +246,7 @@ static int decode_ffn_t(const moe_shape& s, const moe_weights& w, const void* x,
         a.seg[0] = GemvSeg{w.rg, w.ru, (long long)r * d, x, x, 0, 0, d};
         a.rows = r; a.k = k; a.E = s.n_experts; a.idx = idx; a.gate = gate; a.out0 = tg; a.out1 = tu;
         if ((rc = launch_gemv<T>(a, GEMV_DUAL, st)) != MOE_OK) return rc;
+        stage_mark(timer, "gemv_rank_gate_up");
     }
     {  // hidden vector h_j = silu(M_gate x) * (M_up x)
         a = GemvArgs{};
@@ -255,6 +256,7 @@ static int decode_ffn_t(const moe_shape& s, const moe_weights& w, const void* x,
         a.nseg = ns;
         a.rows = F; a.k = k; a.E = s.n_experts; a.idx = idx; a.gate = gate; a.out0 = h;
         if ((rc = launch_gemv<T>(a, GEMV_SWIGLU, st)) != MOE_OK) return rc;
+        stage_mark(timer, "gemv_gate_up_swiglu");
     }
     if (r > 0) {  // td_j = R_d h_j
         a = GemvArgs{};
@@ -262,6 +264,7 @@ static int decode_ffn_t(const moe_shape& s, const moe_weights& w, const void* x,
         a.seg[0] = GemvSeg{w.rd, nullptr, (long long)r * F, h, h, 1, F, F};
         a.rows = r; a.k = k; a.E = s.n_experts; a.idx = idx; a.gate = gate; a.out0 = td;
         if ((rc = launch_gemv<T>(a, GEMV_PLAIN, st)) != MOE_OK) return rc;
+        stage_mark(timer, "gemv_rank_down");
     }
     {  // y = sum_j gate_j M_down h_j (+ x)
         a = GemvArgs{};
@@ -272,16 +275,17 @@ static int decode_ffn_t(const moe_shape& s, const moe_weights& w, const void* x,
         a.rows = d; a.k = k; a.E = s.n_experts; a.idx = idx; a.gate = gate; a.y = y;
         a.residual = (s.flags & MOE_FLAG_RESIDUAL) ? x : nullptr;
         if ((rc = launch_gemv<T>(a, GEMV_COMBINE, st)) != MOE_OK) return rc;
+        stage_mark(timer, "gemv_down_combine");
     }
     return MOE_OK;
 }
 
 int launch_decode_ffn(const moe_shape& s, const moe_weights& w, const void* x,
                       const int32_t* topk_idx, const float* topk_gate, void* y, void* scratch,
-                      hipStream_t st) {
+                      hipStream_t st, StageTimer* timer) {
     if (s.act_dtype == MOE_F32)
-        return decode_ffn_t<float>(s, w, x, topk_idx, topk_gate, y, scratch, st);
-    return decode_ffn_t<bf16_t>(s, w, x, topk_idx, topk_gate, y, scratch, st);
+        return decode_ffn_t<float>(s, w, x, topk_idx, topk_gate, y, scratch, st, timer);
+    return decode_ffn_t<bf16_t>(s, w, x, topk_idx, topk_gate, y, scratch, st, timer);
 }
 
 }  // namespace moe

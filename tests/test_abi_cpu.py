@@ -18,7 +18,7 @@ def _declared():
 
 def test_library_exports_every_declared_symbol():
     names = _declared()
-    assert set(names) == set(pkg.EXPORTS) and len(names) == 8
+    assert set(names) == set(pkg.EXPORTS) and len(names) == 9
     L = pkg.lib()
     for n in names:
         assert getattr(L, n) is not None
