@@ -48,6 +48,42 @@ struct GemmArgs {
     int n_tiles;
 };
 
+// Workgroup -> output tile.  Tiles are ordered expert-major, then n-tile, then the expert's
+// own m-tiles, so neighbouring tiles share the expert's activation rows (and, for equal
+// n-tile, its weight tile).  Workgroups are handed to the 8 XCDs round-robin by id; XCD x
+// takes the x-th contiguous eighth of that order, which keeps each XCD's L2 working set to
+// about one expert's rows plus the weight tiles it is streaming.  The grid is an upper
+// bound (group sizes live on the device); surplus workgroups return false.
+__device__ __forceinline__ bool find_tile(const int32_t* __restrict__ offsets, int E, int BM,
+                                          int n_tiles, int& e_out, int& row0, int& row_end,
+                                          int& nt_out) {
+    int total = 0;
+    for (int e = 0; e < E; ++e) total += (offsets[e + 1] - offsets[e] + BM - 1) / BM;
+    total *= n_tiles;
+    const int per_xcd = (total + 7) / 8;
+    const int slot = blockIdx.x >> 3;
+    const int L = (blockIdx.x & 7) * per_xcd + slot;
+    if (slot >= per_xcd || L >= total) return false;
+    int before = 0;
+    int prev = offsets[0];
+    for (int e = 0; e < E; ++e) {
+        const int next = offsets[e + 1];
+        const int mtiles = (next - prev + BM - 1) / BM;
+        const int here = mtiles * n_tiles;
+        if (L < before + here) {
+            const int local = L - before;
+            e_out = e;
+            nt_out = local / mtiles;
+            row0 = prev + (local % mtiles) * BM;
+            row_end = next;
+            return true;
+        }
+        before += here;
+        prev = next;
+    }
+    return false;
+}
+
 // m-tile index (over all experts, in expert order) -> expert and row range
 __device__ __forceinline__ bool find_m_tile(const int32_t* __restrict__ offsets, int E, int BM,
                                             int mt, int& e_out, int& row0, int& row_end) {
@@ -75,39 +111,39 @@ __device__ __forceinline__ int src_row(const GemmArgs& g, const GemmSeg& sg, int
 }
 
 // ============================================================================= bf16 MFMA
-constexpr int BK = 64;  // k elements per LDS tile row = 128 bytes = 8 chunks of 16 bytes
-
+// LDS tile rows hold BK bf16 (BK/8 chunks of 16 bytes).  The chunk index is XOR-ed with a
+// function of the row chosen so that 16 consecutive rows read at one chunk index (an MFMA
+// operand read) touch 16 distinct 16-byte bank groups, as do the row-wise fills.
+template <int BK>
 __device__ __forceinline__ int lds_off(int row, int chunk) {
-    return row * (BK * 2) + ((chunk ^ ((row >> 1) & 7)) << 4);
+    constexpr int CPR = BK / 8;  // chunks per row
+    return row * (BK * 2) + ((chunk ^ ((row / (16 / CPR)) % CPR)) << 4);
 }
 
-template <int BM, int BN, int WM, int WN, bool SWIGLU, bool DUAL_A>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmArgs g) {
+template <int BM, int BN, int BK, int WM, int WN, bool SWIGLU, bool DUAL_A>
+__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(const GemmArgs g) {
     constexpr int WAVES_N = BN / WN;
-    static_assert((BM / WM) * WAVES_N == 4, "four waves per workgroup");
+    constexpr int NTHR = (BM / WM) * WAVES_N * 64;
     constexpr int MT = WM / 32, NT = WN / 32;
     static_assert(!SWIGLU || NT % 2 == 0, "gate and up fragments pair up");
-    constexpr int AI = BM / 32, BI = BN / 32;  // 16-byte chunks per thread per tile
+    constexpr int CPR = BK / 8;
+    constexpr int RPP = NTHR / CPR;            // tile rows filled per pass of the workgroup
+    static_assert(BM % RPP == 0 && BN % RPP == 0 && (BN / 2) % RPP == 0, "fill passes");
+    constexpr int AI = BM / RPP, BI = BN / RPP;  // 16-byte chunks per thread per tile
     constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
     constexpr int STAGE = A_BYTES * (DUAL_A ? 2 : 1) + B_BYTES;
     extern __shared__ __align__(16) char smem[];
 
     // ---- which tile --------------------------------------------------------------------------
-    const int total = g.m_tiles_max * g.n_tiles;
-    const int per_xcd = (gridDim.x + 7) / 8;
-    const int L = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (L >= total) return;
-    const int mt = L % g.m_tiles_max;
-    const int nt = L / g.m_tiles_max;
-    int e, row0, row_end;
-    if (!find_m_tile(g.offsets, g.E, BM, mt, e, row0, row_end)) return;
+    int e, row0, row_end, nt;
+    if (!find_tile(g.offsets, g.E, BM, g.n_tiles, e, row0, row_end, nt)) return;
     constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;  // output columns per block
     const int n0 = nt * BN_OUT;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-    const int ld_row = tid >> 3, ld_chunk = tid & 7;
+    const int ld_row = tid / CPR, ld_chunk = tid % CPR;
 
     f32x16 acc[MT][NT];
 #pragma unroll
@@ -130,12 +166,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmArgs g) {
         long long aoff[AI], boff[BI];
 #pragma unroll
         for (int i = 0; i < AI; ++i) {
-            const int s = row0 + ld_row + 32 * i;
+            const int s = row0 + ld_row + RPP * i;
             aoff[i] = s < row_end ? (long long)src_row(g, sg, s) * K : -1;
         }
 #pragma unroll
         for (int i = 0; i < BI; ++i) {
-            const int j = ld_row + 32 * i;
+            const int j = ld_row + RPP * i;
             const int n = SWIGLU ? n0 + (j % (BN / 2)) : n0 + j;
             boff[i] = n < g.N ? (long long)n * K : -1;
         }
@@ -165,14 +201,14 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmArgs g) {
             char* base = smem + stage * STAGE;
 #pragma unroll
             for (int i = 0; i < AI; ++i) {
-                *reinterpret_cast<bf16x8*>(base + lds_off(ld_row + 32 * i, ld_chunk)) = ra[i];
+                *reinterpret_cast<bf16x8*>(base + lds_off<BK>(ld_row + RPP * i, ld_chunk)) = ra[i];
                 if (DUAL_A && dual)
-                    *reinterpret_cast<bf16x8*>(base + A_BYTES + lds_off(ld_row + 32 * i, ld_chunk)) = ra1[i];
+                    *reinterpret_cast<bf16x8*>(base + A_BYTES + lds_off<BK>(ld_row + RPP * i, ld_chunk)) = ra1[i];
             }
             char* bb = base + A_BYTES * (DUAL_A ? 2 : 1);
 #pragma unroll
             for (int i = 0; i < BI; ++i)
-                *reinterpret_cast<bf16x8*>(bb + lds_off(ld_row + 32 * i, ld_chunk)) = rb[i];
+                *reinterpret_cast<bf16x8*>(bb + lds_off<BK>(ld_row + RPP * i, ld_chunk)) = rb[i];
         };
 
         const int nk = (K + BK - 1) / BK;
@@ -194,8 +230,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmArgs g) {
 #pragma unroll
                 for (int mi = 0; mi < MT; ++mi) {
                     const int r = wm * WM + mi * 32 + (lane & 31);
-                    fa[mi] = *reinterpret_cast<const bf16x8*>(a0b + lds_off(r, chunk));
-                    if (DUAL_A) fa1[mi] = *reinterpret_cast<const bf16x8*>(a1b + lds_off(r, chunk));
+                    fa[mi] = *reinterpret_cast<const bf16x8*>(a0b + lds_off<BK>(r, chunk));
+                    if (DUAL_A) fa1[mi] = *reinterpret_cast<const bf16x8*>(a1b + lds_off<BK>(r, chunk));
                 }
 #pragma unroll
                 for (int ni = 0; ni < NT; ++ni) {
@@ -204,7 +240,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmArgs g) {
                         r = (ni < NT / 2 ? 0 : BN / 2) + wn * (WN / 2) + (ni % (NT / 2)) * 32 + (lane & 31);
                     else
                         r = wn * WN + ni * 32 + (lane & 31);
-                    fb[ni] = *reinterpret_cast<const bf16x8*>(bb + lds_off(r, chunk));
+                    fb[ni] = *reinterpret_cast<const bf16x8*>(bb + lds_off<BK>(r, chunk));
                 }
 #pragma unroll
                 for (int mi = 0; mi < MT; ++mi)
@@ -221,6 +257,182 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmArgs g) {
 
     // ---- epilogue: accumulator element i of a 32x32 block sits at
     //      row (i/4)*8 + (lane/32)*4 + i%4, column lane%32 ---------------------------------------
+    bf16_t* C = static_cast<bf16_t*>(g.C);
+#pragma unroll
+    for (int mi = 0; mi < MT; ++mi) {
+#pragma unroll
+        for (int ni = 0; ni < (SWIGLU ? NT / 2 : NT); ++ni) {
+            const int col = n0 + wn * (SWIGLU ? WN / 2 : WN) + ni * 32 + (lane & 31);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int row = row0 + wm * WM + mi * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
+                if (row < row_end && col < g.N) {
+                    float v = acc[mi][ni][i];
+                    if (SWIGLU) v = silu_f32(v) * acc[mi][ni + NT / 2][i];
+                    C[(size_t)row * g.N + col] = (bf16_t)v;
+                }
+            }
+        }
+    }
+}
+
+// ============================================================================= bf16 MFMA, deep pipeline
+// Fast path for K multiples of BK.  Same tiling and swizzled LDS layout as
+// gemm_bf16_kernel, but with two register sets and two LDS stages, so three tiles are in
+// flight: tile kt is multiplied out of LDS while tile kt+1 waits in registers to be
+// written to the other LDS stage at the end of the step and tile kt+2 is being fetched.
+// That puts two full steps of MFMA work between issuing a global load and first needing
+// its data.  Loads are unconditional (rows past the end of a group / matrix are clamped to
+// its last row and only feed outputs the epilogue never stores), so the loop has no
+// divergent control flow.  (Direct global->LDS loads were measured here and rejected:
+// on this chip they stall co-issued MFMAs far more than register loads do.)
+template <int BM, int BN, int BK, int WM, int WN, bool SWIGLU, bool DUAL_A>
+__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_deep_kernel(const GemmArgs g) {
+    constexpr int WAVES_N = BN / WN;
+    constexpr int NTHR = (BM / WM) * WAVES_N * 64;
+    constexpr int MT = WM / 32, NT = WN / 32;
+    static_assert(!SWIGLU || NT % 2 == 0, "gate and up fragments pair up");
+    constexpr int CPR = BK / 8;
+    constexpr int RPP = NTHR / CPR;
+    static_assert(BM % RPP == 0 && BN % RPP == 0 && (BN / 2) % RPP == 0, "fill passes");
+    constexpr int AI = BM / RPP, BI = BN / RPP;
+    constexpr int NA = DUAL_A ? 2 : 1;
+    constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
+    constexpr int STAGE = A_BYTES * NA + B_BYTES;
+    extern __shared__ __align__(16) char smem[];
+
+    int e, row0, row_end, nt;
+    if (!find_tile(g.offsets, g.E, BM, g.n_tiles, e, row0, row_end, nt)) return;
+    constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;
+    const int n0 = nt * BN_OUT;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const int ld_row = tid / CPR, ld_chunk = tid % CPR;
+
+    f32x16 acc[MT][NT];
+#pragma unroll
+    for (int mi = 0; mi < MT; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NT; ++ni)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
+
+    struct Regs {
+        bf16x8 a[AI], a1[DUAL_A ? AI : 1], b[BI];
+    };
+
+    for (int sidx = 0; sidx < g.nseg; ++sidx) {
+        const GemmSeg& sg = g.seg[sidx];
+        const int K = sg.K;
+        const bool dual = DUAL_A && sg.A1 != sg.A0;
+        const bf16_t* B0 = static_cast<const bf16_t*>(sg.B0) + (size_t)e * sg.strideB;
+        const bf16_t* B1 = SWIGLU ? static_cast<const bf16_t*>(sg.B1) + (size_t)e * sg.strideB : B0;
+
+        const bf16_t* pa[AI];
+        const bf16_t* pa1[DUAL_A ? AI : 1];
+        const bf16_t* pb[BI];
+#pragma unroll
+        for (int i = 0; i < AI; ++i) {
+            const int s = min(row0 + ld_row + RPP * i, row_end - 1);
+            const size_t off = (size_t)src_row(g, sg, s) * K + ld_chunk * 8;
+            pa[i] = static_cast<const bf16_t*>(sg.A0) + off;
+            if (DUAL_A) pa1[i] = static_cast<const bf16_t*>(sg.A1) + off;
+        }
+#pragma unroll
+        for (int i = 0; i < BI; ++i) {
+            const int j = ld_row + RPP * i;
+            const int n = min(SWIGLU ? n0 + (j % (BN / 2)) : n0 + j, g.N - 1);
+            pb[i] = ((SWIGLU && i >= BI / 2) ? B1 : B0) + (size_t)n * K + ld_chunk * 8;
+        }
+
+        auto gload = [&](Regs& r, int k0) {
+#pragma unroll
+            for (int i = 0; i < AI; ++i) {
+                r.a[i] = *reinterpret_cast<const bf16x8*>(pa[i] + k0);
+                if (DUAL_A && dual) r.a1[i] = *reinterpret_cast<const bf16x8*>(pa1[i] + k0);
+            }
+#pragma unroll
+            for (int i = 0; i < BI; ++i) r.b[i] = *reinterpret_cast<const bf16x8*>(pb[i] + k0);
+        };
+        auto lstore = [&](int stage, const Regs& r) {
+            char* base = smem + stage * STAGE;
+#pragma unroll
+            for (int i = 0; i < AI; ++i) {
+                *reinterpret_cast<bf16x8*>(base + lds_off<BK>(ld_row + RPP * i, ld_chunk)) = r.a[i];
+                if (DUAL_A && dual)
+                    *reinterpret_cast<bf16x8*>(base + A_BYTES + lds_off<BK>(ld_row + RPP * i, ld_chunk)) = r.a1[i];
+            }
+            char* bb = base + A_BYTES * NA;
+#pragma unroll
+            for (int i = 0; i < BI; ++i)
+                *reinterpret_cast<bf16x8*>(bb + lds_off<BK>(ld_row + RPP * i, ld_chunk)) = r.b[i];
+        };
+        auto compute = [&](int stage) {
+            const char* base = smem + stage * STAGE;
+            const char* a0b = base;
+            const char* a1b = (DUAL_A && dual) ? base + A_BYTES : base;
+            const char* bb = base + A_BYTES * NA;
+#pragma unroll
+            for (int ks = 0; ks < BK / 16; ++ks) {
+                const int chunk = ks * 2 + (lane >> 5);
+                bf16x8 fa[MT], fa1[DUAL_A ? MT : 1], fb[NT];
+#pragma unroll
+                for (int mi = 0; mi < MT; ++mi) {
+                    const int r = wm * WM + mi * 32 + (lane & 31);
+                    fa[mi] = *reinterpret_cast<const bf16x8*>(a0b + lds_off<BK>(r, chunk));
+                    if (DUAL_A) fa1[mi] = *reinterpret_cast<const bf16x8*>(a1b + lds_off<BK>(r, chunk));
+                }
+#pragma unroll
+                for (int ni = 0; ni < NT; ++ni) {
+                    int r;
+                    if (SWIGLU)
+                        r = (ni < NT / 2 ? 0 : BN / 2) + wn * (WN / 2) + (ni % (NT / 2)) * 32 + (lane & 31);
+                    else
+                        r = wn * WN + ni * 32 + (lane & 31);
+                    fb[ni] = *reinterpret_cast<const bf16x8*>(bb + lds_off<BK>(r, chunk));
+                }
+#pragma unroll
+                for (int mi = 0; mi < MT; ++mi)
+#pragma unroll
+                    for (int ni = 0; ni < NT; ++ni) {
+                        const bf16x8 av = (DUAL_A && SWIGLU && ni >= NT / 2) ? fa1[mi] : fa[mi];
+                        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, fb[ni], acc[mi][ni], 0, 0, 0);
+                    }
+            }
+        };
+
+        const int nk = K / BK;
+        const int k_last = K - BK;
+        Regs r0, r1;
+        // Every load and LDS write below is unconditional (k offsets are clamped to the last
+        // tile, whose re-fetch near the end is harmless): the outstanding-load count at each
+        // wait is then a compile-time constant and a wait for tile kt+1 never also waits for
+        // the younger loads of tile kt+2.
+        __syncthreads();  // the previous segment's readers are done with both stages
+        gload(r0, 0);
+        gload(r1, min(BK, k_last));
+        lstore(0, r0);
+        __syncthreads();
+        for (int kt = 0; kt < nk; kt += 2) {
+            // even step: multiply tile kt (stage 0); r0 is free, r1 holds tile kt+1
+            gload(r0, min((kt + 2) * BK, k_last));
+            compute(0);
+            __builtin_amdgcn_sched_barrier(0);
+            lstore(1, r1);
+            __syncthreads();
+            if (kt + 1 >= nk) break;
+            // odd step: multiply tile kt+1 (stage 1); r1 is free, r0 holds tile kt+2
+            gload(r1, min((kt + 3) * BK, k_last));
+            compute(1);
+            __builtin_amdgcn_sched_barrier(0);
+            lstore(0, r0);
+            __syncthreads();
+        }
+    }
+
+    // ---- epilogue (accumulator layout as in gemm_bf16_kernel) -------------------------------------
     bf16_t* C = static_cast<bf16_t*>(g.C);
 #pragma unroll
     for (int mi = 0; mi < MT; ++mi) {
@@ -300,15 +512,16 @@ __global__ __launch_bounds__(256) void gemm_simple_kernel(const GemmArgs g) {
 }
 
 // ============================================================================= host side
-template <int BM, int BN, int WM, int WN, bool SWIGLU, bool DUAL_A>
+template <int BM, int BN, int BK, int WM, int WN, bool SWIGLU, bool DUAL_A>
 static int launch_bf16(GemmArgs& g, hipStream_t st) {
     constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;
+    constexpr int NTHR = (BM / WM) * (BN / WN) * 64;
     g.m_tiles_max = g.P / BM + g.E;
     g.n_tiles = (g.N + BN_OUT - 1) / BN_OUT;
     const int total = g.m_tiles_max * g.n_tiles;
     const int grid = (total + 7) / 8 * 8;
     constexpr size_t lds = 2 * ((size_t)BM * BK * 2 * (DUAL_A ? 2 : 1) + (size_t)BN * BK * 2);
-    auto kern = gemm_bf16_kernel<BM, BN, WM, WN, SWIGLU, DUAL_A>;
+    auto kern = gemm_bf16_kernel<BM, BN, BK, WM, WN, SWIGLU, DUAL_A>;
     static bool attr_set = false;
     if (lds > 32 * 1024 && !attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -316,7 +529,29 @@ static int launch_bf16(GemmArgs& g, hipStream_t st) {
             return MOE_ERR_LAUNCH;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, g);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(NTHR), lds, st, g);
+    return launch_status();
+}
+
+template <int BM, int BN, int BK, int WM, int WN, bool SWIGLU, bool DUAL_A>
+static int launch_bf16_deep(GemmArgs& g, hipStream_t st) {
+    constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;
+    constexpr int NTHR = (BM / WM) * (BN / WN) * 64;
+    g.m_tiles_max = g.P / BM + g.E;
+    g.n_tiles = (g.N + BN_OUT - 1) / BN_OUT;
+    const int total = g.m_tiles_max * g.n_tiles;
+    const int grid = (total + 7) / 8 * 8;
+    constexpr size_t lds = 2 * ((size_t)BM * BK * 2 * (DUAL_A ? 2 : 1) + (size_t)BN * BK * 2);
+    static_assert(lds <= 160 * 1024, "LDS stages exceed the CU's 160 KB");
+    auto kern = gemm_bf16_deep_kernel<BM, BN, BK, WM, WN, SWIGLU, DUAL_A>;
+    static bool attr_set = false;
+    if (lds > 32 * 1024 && !attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+            return MOE_ERR_LAUNCH;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(NTHR), lds, st, g);
     return launch_status();
 }
 
@@ -333,12 +568,21 @@ static int run_gemm(const moe_shape& s, GemmArgs& g, bool swiglu, hipStream_t st
     if (g.P == 0) return MOE_OK;
     if (s.act_dtype == MOE_F32)
         return swiglu ? launch_simple<float, true>(g, st) : launch_simple<float, false>(g, st);
-    bool dual = false;
-    for (int i = 0; i < g.nseg; ++i) dual |= swiglu && g.seg[i].A1 != g.seg[i].A0;
+    bool dual = false, fast = true;
+    for (int i = 0; i < g.nseg; ++i) {
+        dual |= swiglu && g.seg[i].A1 != g.seg[i].A0;
+        fast &= g.seg[i].K % 64 == 0;  // the deep pipeline has no K tail
+    }
+    if (fast) {
+        if (swiglu)
+            return dual ? launch_bf16_deep<128, 128, 64, 64, 64, true, true>(g, st)
+                        : launch_bf16_deep<128, 128, 64, 64, 64, true, false>(g, st);
+        return launch_bf16_deep<128, 128, 64, 64, 64, false, false>(g, st);
+    }
     if (swiglu)
-        return dual ? launch_bf16<128, 128, 64, 64, true, true>(g, st)
-                    : launch_bf16<128, 128, 64, 64, true, false>(g, st);
-    return launch_bf16<128, 128, 64, 64, false, false>(g, st);
+        return dual ? launch_bf16<128, 128, 64, 64, 64, true, true>(g, st)
+                    : launch_bf16<128, 128, 64, 64, 64, true, false>(g, st);
+    return launch_bf16<128, 128, 64, 64, 64, false, false>(g, st);
 }
 
 // scratch: h [P,F], then (rank > 0) tg, tu, td [P,r], all in the activation type
