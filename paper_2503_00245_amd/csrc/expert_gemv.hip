@@ -15,8 +15,9 @@
 // A segment whose matrix is shared by all experts (the shared dense base) is read once
 // per row, not once per pair: with a shared input vector its product is reused for every
 // pair; in COMBINE the pairs' inputs are pre-mixed with the gates (linearity).
-// Input vectors are staged once per workgroup in LDS as fp32; a wave reads a matrix row
-// with 16-byte loads, 1 KB per instruction, and reduces with a 64-lane butterfly.
+// A wave reads a matrix row with 16-byte loads, 1 KB per instruction, two in flight, takes
+// the matching slice of the input vector straight from L1/L2, and reduces with a 64-lane
+// butterfly.  Nothing is staged in LDS, so the weight stream starts at once.
 #include "common.h"
 
 namespace moe {
@@ -24,7 +25,10 @@ namespace moe {
 enum { GEMV_PLAIN = 0, GEMV_DUAL = 1, GEMV_SWIGLU = 2, GEMV_COMBINE = 3 };
 constexpr int kGemvThreads = 512;
 constexpr int kGemvWaves = kGemvThreads / kWave;
-constexpr size_t kGemvMaxLds = 64 * 1024;
+// Chunk loads a wave issues before consuming the first.  Measured on MI355X: 2 beats 1, 4
+// and 8 -- many resident waves (about 60 VGPRs, 8 per SIMD) with few loads each stream
+// faster than few waves with many loads each.
+constexpr int kBatch = 2;
 
 struct GemvSeg {
     const void* W0;      // [Eb, rows, n]
@@ -43,6 +47,7 @@ struct GemvArgs {
     int rows;
     int k;
     int rows_per_wave;
+    int slices;           // waves per row: 1, 2, 4 or 8
     int E;
     const int32_t* idx;   // [k] selected experts
     const float* gate;    // [k]
@@ -52,147 +57,254 @@ struct GemvArgs {
     const void* residual; // [rows] or NULL (COMBINE)
 };
 
+// Where a stage's input vector comes from.  Vectors are read straight from global memory
+// with the same 16-byte lane layout as the matrix row (they are a few KB, so they sit in
+// L1/L2): no LDS staging, no barrier, and the weight stream starts with the first
+// instruction of every wave.
+struct VecSrc {
+    const void* p;       // first element of this pair's vector
+    int is_f32;          // 1: fp32 scratch vector, 0: activation type
+    int nmix;            // 0: plain vector; else the gate-weighted mix of nmix vectors
+    int mix_stride;      // elements between the mixed vectors
+    const float* mix_w;  // [nmix] weights (the gates)
+};
+
 template <typename T>
-__device__ __forceinline__ float row_dot(const T* __restrict__ wrow, const float* v, int n,
-                                         int lane) {
+__device__ __forceinline__ void load_vec_raw(const void* p, int is_f32, int off,
+                                             float (&out)[Store<T>::VEC]) {
     typedef Store<T> S;
-    constexpr int VEC = S::VEC;
-    float acc = 0.f;
-#pragma unroll 4
-    for (int c = lane * VEC; c < n; c += kWave * VEC) {
-        const typename S::vec_t w =
-            __builtin_nontemporal_load(reinterpret_cast<const typename S::vec_t*>(wrow + c));
+    if (is_f32) {
 #pragma unroll
-        for (int q = 0; q < VEC; q += 4) {
-            const f32x4 vv = *reinterpret_cast<const f32x4*>(v + c + q);
-            acc = fmaf(S::get(w, q + 0), vv[0], acc);
-            acc = fmaf(S::get(w, q + 1), vv[1], acc);
-            acc = fmaf(S::get(w, q + 2), vv[2], acc);
-            acc = fmaf(S::get(w, q + 3), vv[3], acc);
+        for (int q = 0; q < S::VEC; q += 4) {
+            const f32x4 t = *reinterpret_cast<const f32x4*>(static_cast<const float*>(p) + off + q);
+            out[q] = t[0]; out[q + 1] = t[1]; out[q + 2] = t[2]; out[q + 3] = t[3];
         }
+    } else {
+        const typename S::vec_t t = *reinterpret_cast<const typename S::vec_t*>(static_cast<const T*>(p) + off);
+#pragma unroll
+        for (int q = 0; q < S::VEC; ++q) out[q] = S::get(t, q);
+    }
+}
+
+enum { VK_ACT = 0, VK_F32 = 1, VK_MIX = 2 };  // activation-typed / fp32 scratch / gate-mixed fp32
+
+template <typename T, int VK>
+__device__ __forceinline__ void load_vec(const VecSrc& v, int off, float (&out)[Store<T>::VEC]) {
+    constexpr int VEC = Store<T>::VEC;
+    if (VK != VK_MIX) {
+        load_vec_raw<T>(v.p, VK == VK_F32, off, out);
+        return;
+    }
+#pragma unroll
+    for (int q = 0; q < VEC; ++q) out[q] = 0.f;
+    for (int j = 0; j < v.nmix; ++j) {
+        float t[VEC];
+        load_vec_raw<T>(v.p, 1, j * v.mix_stride + off, t);
+        const float g = v.mix_w[j];
+#pragma unroll
+        for (int q = 0; q < VEC; ++q) out[q] = fmaf(g, t[q], out[q]);
+    }
+}
+
+// Lane-partial dot of one matrix row with a vector.  The row is cut into 1 KB chunks
+// (64 lanes x 16 bytes); with `slices` > 1 this wave takes chunks slice, slice + slices, ...
+// kBatch chunk loads (and their vector loads) are issued back to back before any is consumed.
+template <typename T, int VK>
+__device__ __forceinline__ float row_dot_k(const T* __restrict__ wrow, const VecSrc& v, int n,
+                                           int lane, int slice, int slices) {
+    typedef Store<T> S;
+    typedef typename S::vec_t vec_t;
+    constexpr int VEC = S::VEC;
+    constexpr int CH = kWave * VEC;
+    const int nfull = n / CH;
+    const int lo = lane * VEC;
+    float acc = 0.f;
+    auto fma_chunk = [&](const vec_t& w, const float (&x)[VEC]) {
+#pragma unroll
+        for (int q = 0; q < VEC; ++q) acc = fmaf(S::get(w, q), x[q], acc);
+    };
+    auto load_chunk = [&](int c) {
+        return __builtin_nontemporal_load(reinterpret_cast<const vec_t*>(wrow + c * CH + lo));
+    };
+    int c = slice;
+    for (; c + (kBatch - 1) * slices < nfull; c += kBatch * slices) {
+        vec_t w[kBatch];
+        float x[kBatch][VEC];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) w[u] = load_chunk(c + u * slices);
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) load_vec<T, VK>(v, (c + u * slices) * CH + lo, x[u]);
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) fma_chunk(w[u], x[u]);
+    }
+    for (; c < nfull; c += slices) {
+        const vec_t w0 = load_chunk(c);
+        float x0[VEC];
+        load_vec<T, VK>(v, c * CH + lo, x0);
+        fma_chunk(w0, x0);
+    }
+    // ragged tail chunk (n is a multiple of VEC, so a lane is entirely in or out of it)
+    if (c == nfull && nfull * CH + lo < n) {
+        const vec_t w0 = load_chunk(nfull);
+        float x0[VEC];
+        load_vec<T, VK>(v, nfull * CH + lo, x0);
+        fma_chunk(w0, x0);
     }
     return acc;
 }
 
 template <typename T>
-__device__ __forceinline__ float load_vec_elem(const void* v, int is_f32, size_t i) {
-    return is_f32 ? static_cast<const float*>(v)[i] : Store<T>::to_f32(static_cast<const T*>(v)[i]);
+__device__ __forceinline__ float row_dot(const T* __restrict__ wrow, const VecSrc& v, int n,
+                                         int lane, int slice, int slices) {
+    // wave-uniform dispatch on the vector kind, outside the streaming loop
+    if (v.nmix) return row_dot_k<T, VK_MIX>(wrow, v, n, lane, slice, slices);
+    if (v.is_f32) return row_dot_k<T, VK_F32>(wrow, v, n, lane, slice, slices);
+    return row_dot_k<T, VK_ACT>(wrow, v, n, lane, slice, slices);
 }
 
+// Workgroup = 8 waves = (8 / slices) rows x `slices` waves per row.  Short stages (few rows)
+// use several waves per row so that every CU still has tens of waves with loads in flight;
+// the per-slice sums meet in LDS and are added in slice order (deterministic).
 template <typename T, int MODE>
 __global__ __launch_bounds__(kGemvThreads) void gemv_kernel(const GemvArgs a) {
-    extern __shared__ __align__(16) float lds[];
+    __shared__ float s_part[kGemvWaves][2 * kMaxExperts + 2];
     constexpr bool DUAL = (MODE == GEMV_DUAL || MODE == GEMV_SWIGLU);
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     const int k = a.k;
+    const int slices = a.slices;
+    const int slice = wave % slices;
+    const int local_row = wave / slices;
 
-    // ---- stage the input vectors ------------------------------------------------------------
-    const float* sv0[2];
-    const float* sv1[2];
     bool once[2];  // segment evaluated once per row (shared matrix and one effective vector)
-    {
-        float* cur = lds;
-        for (int s = 0; s < a.nseg; ++s) {
-            const GemvSeg& g = a.seg[s];
-            const bool premix = (MODE == GEMV_COMBINE) && g.stride == 0 && g.vstride != 0;
-            once[s] = g.stride == 0 && (g.vstride == 0 || premix);
-            const int nv = (g.vstride == 0 || premix) ? 1 : k;
-            sv0[s] = cur;
-            if (premix) {
-                for (int i = threadIdx.x; i < g.n; i += kGemvThreads) {
-                    float m = 0.f;
-                    for (int j = 0; j < k; ++j)
-                        m = fmaf(a.gate[j], load_vec_elem<T>(g.v0, g.v_is_f32, (size_t)j * g.vstride + i), m);
-                    cur[i] = m;
-                }
-            } else {
-                for (int i = threadIdx.x; i < nv * g.n; i += kGemvThreads) {
-                    const int j = i / g.n;
-                    cur[i] = load_vec_elem<T>(g.v0, g.v_is_f32, (size_t)j * g.vstride + (i - j * g.n));
-                }
-            }
-            cur += nv * g.n;
-            sv1[s] = sv0[s];
-            if (DUAL && g.v1 != g.v0) {
-                sv1[s] = cur;
-                for (int i = threadIdx.x; i < nv * g.n; i += kGemvThreads) {
-                    const int j = i / g.n;
-                    cur[i] = load_vec_elem<T>(g.v1, g.v_is_f32, (size_t)j * g.vstride + (i - j * g.n));
-                }
-                cur += nv * g.n;
-            }
-        }
+    bool premix[2];
+    for (int s = 0; s < a.nseg; ++s) {
+        const GemvSeg& g = a.seg[s];
+        premix[s] = (MODE == GEMV_COMBINE) && g.stride == 0 && g.vstride != 0;
+        once[s] = g.stride == 0 && (g.vstride == 0 || premix[s]);
     }
-    __syncthreads();
+    auto vec_of = [&](const GemvSeg& g, const void* base, int j, bool mix) {
+        VecSrc v;
+        const size_t es = g.v_is_f32 ? 4 : sizeof(T);
+        v.p = static_cast<const char*>(base) + (size_t)j * g.vstride * es;
+        v.is_f32 = g.v_is_f32;
+        v.nmix = mix ? k : 0;
+        v.mix_stride = g.vstride;
+        v.mix_w = a.gate;
+        return v;
+    };
 
-    const int gw = blockIdx.x * kGemvWaves + wave;
-    const int row_end = min(a.rows, (gw + 1) * a.rows_per_wave);
-    for (int row = gw * a.rows_per_wave; row < row_end; ++row) {
-        // segments read once per row
+    const int rows_per_block = kGemvWaves / slices;
+    const int row0 = (blockIdx.x * rows_per_block + local_row) * a.rows_per_wave;
+    // rows_per_wave is 1 whenever slices > 1, so the barrier below is reached once by all
+    for (int ri = 0; ri < a.rows_per_wave; ++ri) {
+        const int row = row0 + ri;
+        const bool active = row < a.rows;
+        float* part = s_part[wave];
+        // per-slice sums of this row: [0],[1] segments read once per row; [2+2j],[3+2j] pair j
         float sh0 = 0.f, sh1 = 0.f;
-        for (int s = 0; s < a.nseg; ++s) {
-            if (!once[s]) continue;
-            const GemvSeg& g = a.seg[s];
-            sh0 += row_dot<T>(static_cast<const T*>(g.W0) + (size_t)row * g.n, sv0[s], g.n, lane);
-            if (DUAL)
-                sh1 += row_dot<T>(static_cast<const T*>(g.W1) + (size_t)row * g.n, sv1[s], g.n, lane);
-        }
-        float total = (MODE == GEMV_COMBINE) ? wave_sum(sh0) : 0.f;
-        for (int j = 0; j < k; ++j) {
-            const int e = min(max(a.idx[j], 0), a.E - 1);
-            float acc0 = (MODE == GEMV_COMBINE) ? 0.f : sh0;
-            float acc1 = sh1;
+        if (active) {
             for (int s = 0; s < a.nseg; ++s) {
-                if (once[s]) continue;
+                if (!once[s]) continue;
                 const GemvSeg& g = a.seg[s];
-                const size_t woff = (size_t)e * g.stride + (size_t)row * g.n;
-                const int voff = g.vstride ? j * g.n : 0;
-                acc0 += row_dot<T>(static_cast<const T*>(g.W0) + woff, sv0[s] + voff, g.n, lane);
+                sh0 += row_dot<T>(static_cast<const T*>(g.W0) + (size_t)row * g.n,
+                                  vec_of(g, g.v0, 0, premix[s]), g.n, lane, slice, slices);
                 if (DUAL)
-                    acc1 += row_dot<T>(static_cast<const T*>(g.W1) + woff, sv1[s] + voff, g.n, lane);
+                    sh1 += row_dot<T>(static_cast<const T*>(g.W1) + (size_t)row * g.n,
+                                      vec_of(g, g.v1, 0, premix[s]), g.n, lane, slice, slices);
+            }
+        }
+        sh0 = wave_sum(sh0);
+        if (DUAL) sh1 = wave_sum(sh1);
+        float total = sh0;  // COMBINE, single slice
+        for (int j = 0; j < k; ++j) {
+            float acc0 = 0.f, acc1 = 0.f;
+            if (active) {
+                const int e = min(max(a.idx[j], 0), a.E - 1);
+                for (int s = 0; s < a.nseg; ++s) {
+                    if (once[s]) continue;
+                    const GemvSeg& g = a.seg[s];
+                    const size_t woff = (size_t)e * g.stride + (size_t)row * g.n;
+                    acc0 += row_dot<T>(static_cast<const T*>(g.W0) + woff, vec_of(g, g.v0, j, false),
+                                       g.n, lane, slice, slices);
+                    if (DUAL)
+                        acc1 += row_dot<T>(static_cast<const T*>(g.W1) + woff,
+                                           vec_of(g, g.v1, j, false), g.n, lane, slice, slices);
+                }
             }
             acc0 = wave_sum(acc0);
             if (DUAL) acc1 = wave_sum(acc1);
-            if (MODE == GEMV_COMBINE) {
+            if (slices > 1) {
+                if (lane == 0) {
+                    part[2 + 2 * j] = acc0;
+                    part[3 + 2 * j] = acc1;
+                }
+            } else if (MODE == GEMV_COMBINE) {
                 total = fmaf(a.gate[j], acc0, total);
-            } else if (lane == 0) {
+            } else if (lane == 0 && active) {
                 if (MODE == GEMV_SWIGLU) {
-                    a.out0[(size_t)j * a.rows + row] = silu_f32(acc0) * acc1;
+                    a.out0[(size_t)j * a.rows + row] = silu_f32(sh0 + acc0) * (sh1 + acc1);
                 } else {
-                    a.out0[(size_t)j * a.rows + row] = acc0;
-                    if (MODE == GEMV_DUAL) a.out1[(size_t)j * a.rows + row] = acc1;
+                    a.out0[(size_t)j * a.rows + row] = sh0 + acc0;
+                    if (MODE == GEMV_DUAL) a.out1[(size_t)j * a.rows + row] = sh1 + acc1;
                 }
             }
         }
-        if (MODE == GEMV_COMBINE && lane == 0) {
+        if (slices > 1) {
+            if (lane == 0) {
+                part[0] = sh0;
+                part[1] = sh1;
+            }
+            __syncthreads();
+            if (slice == 0 && active) {
+                // lane q sums value q (and q + 64) over the row's slices, in slice order
+                float sum_lo = 0.f, sum_hi = 0.f;
+                for (int sl = 0; sl < slices; ++sl) {
+                    if (lane < 2 + 2 * k) sum_lo += s_part[wave + sl][lane];
+                    if (lane + kWave < 2 + 2 * k) sum_hi += s_part[wave + sl][lane + kWave];
+                }
+                auto value = [&](int q) {
+                    return q < kWave ? __shfl(sum_lo, q, kWave) : __shfl(sum_hi, q - kWave, kWave);
+                };
+                const float t0 = value(0), t1 = value(1);
+                if (MODE == GEMV_COMBINE) {
+                    float tot = t0;
+                    for (int j = 0; j < k; ++j) tot = fmaf(a.gate[j], value(2 + 2 * j), tot);
+                    total = tot;
+                } else {
+                    for (int j = 0; j < k; ++j) {
+                        const float a0 = t0 + value(2 + 2 * j);
+                        const float a1 = t1 + value(3 + 2 * j);
+                        if (lane == 0) {
+                            if (MODE == GEMV_SWIGLU) {
+                                a.out0[(size_t)j * a.rows + row] = silu_f32(a0) * a1;
+                            } else {
+                                a.out0[(size_t)j * a.rows + row] = a0;
+                                if (MODE == GEMV_DUAL) a.out1[(size_t)j * a.rows + row] = a1;
+                            }
+                        }
+                    }
+                }
+            }
+        }
+        if (MODE == GEMV_COMBINE && lane == 0 && active && slice == 0) {
             if (a.residual) total += Store<T>::to_f32(static_cast<const T*>(a.residual)[row]);
             static_cast<T*>(a.y)[row] = Store<T>::from_f32(total);
         }
     }
 }
 
-static size_t gemv_lds_bytes(const GemvArgs& a, int mode) {
-    size_t fl = 0;
-    for (int s = 0; s < a.nseg; ++s) {
-        const GemvSeg& g = a.seg[s];
-        const bool premix = mode == GEMV_COMBINE && g.stride == 0 && g.vstride != 0;
-        const size_t nv = (g.vstride == 0 || premix) ? 1 : (size_t)a.k;
-        const bool dual = (mode == GEMV_DUAL || mode == GEMV_SWIGLU) && g.v1 != g.v0;
-        fl += nv * (size_t)g.n * (dual ? 2 : 1);
-    }
-    return fl * sizeof(float);
-}
-
 template <typename T>
 static int launch_gemv(GemvArgs& a, int mode, hipStream_t st) {
-    const size_t lds = gemv_lds_bytes(a, mode);
-    if (lds > kGemvMaxLds) return MOE_ERR_UNSUPPORTED;
-    // about four workgroups per CU of work, at least one row per wave
-    const int target_waves = 4 * 256 * kGemvWaves;
-    a.rows_per_wave = max(1, min(8, (a.rows + target_waves - 1) / target_waves));
-    const int waves = (a.rows + a.rows_per_wave - 1) / a.rows_per_wave;
-    dim3 grid((waves + kGemvWaves - 1) / kGemvWaves), block(kGemvThreads);
+    const size_t lds = 0;
+    // enough waves that every CU holds tens of them: split rows over several waves when the
+    // stage has few rows, give a wave several rows when it has very many
+    const int want_waves = 256 * 16;
+    a.slices = 1;
+    while (a.k < 63 && a.slices < kGemvWaves && a.rows * a.slices * 2 <= want_waves) a.slices *= 2;
+    a.rows_per_wave = a.slices > 1 ? 1 : max(1, min(8, a.rows / (4 * want_waves)));
+    const int rows_per_block = (kGemvWaves / a.slices) * a.rows_per_wave;
+    dim3 grid((a.rows + rows_per_block - 1) / rows_per_block), block(kGemvThreads);
     switch (mode) {
         case GEMV_PLAIN:
             hipLaunchKernelGGL((gemv_kernel<T, GEMV_PLAIN>), grid, block, lds, st, a);
@@ -216,15 +328,7 @@ size_t decode_scratch_bytes(const moe_shape& s) {
     return round_up(sizeof(float) * k * ((size_t)s.d_ff + 3 * (size_t)s.rank), 256);
 }
 
-bool decode_supported(const moe_shape& s) {
-    if (s.n_tokens != 1) return false;
-    // the largest LDS stage: COMBINE holds k hidden vectors (+ k rank vectors)
-    const size_t k = s.top_k;
-    size_t worst = k * ((size_t)s.d_ff + s.rank);
-    const size_t swiglu = (size_t)s.d_model + 2 * k * (size_t)s.rank;
-    if (swiglu > worst) worst = swiglu;
-    return worst * sizeof(float) <= kGemvMaxLds;
-}
+bool decode_supported(const moe_shape& s) { return s.n_tokens == 1; }
 
 template <typename T>
 static int decode_ffn_t(const moe_shape& s, const moe_weights& w, const void* x,

@@ -6,7 +6,7 @@
 // butterfly, and wave 0 then holds one logit per lane and runs k rounds of a
 // (value, index) arg-max butterfly.  Everything stays in registers / LDS; only the k
 // indices, k gates and (optionally) the E probabilities are written.
-#include "common.h"
+#include "router.h"
 
 namespace moe {
 
@@ -26,60 +26,24 @@ __global__ __launch_bounds__(kRouteWaves* kWave) void route_kernel(
     const int wave = threadIdx.x / kWave;
     const T* xt = x + (size_t)t * d;
 
-    for (int e = wave; e < E; e += kRouteWaves) {
-        const float* we = rw + (size_t)e * d;
-        float acc = 0.f;
-        for (int i = lane * VEC; i < d; i += kWave * VEC) {
-            typename S::vec_t xv = *reinterpret_cast<const typename S::vec_t*>(xt + i);
+    auto load_x = [&](int i, float* out) {
+        const typename S::vec_t xv = *reinterpret_cast<const typename S::vec_t*>(xt + i);
 #pragma unroll
-            for (int q = 0; q < VEC; q += 4) {
-                f32x4 wv = *reinterpret_cast<const f32x4*>(we + i + q);
-                acc = fmaf(S::get(xv, q + 0), wv[0], acc);
-                acc = fmaf(S::get(xv, q + 1), wv[1], acc);
-                acc = fmaf(S::get(xv, q + 2), wv[2], acc);
-                acc = fmaf(S::get(xv, q + 3), wv[3], acc);
-            }
-        }
-        acc = wave_sum(acc);
+        for (int q = 0; q < VEC; ++q) out[q] = S::get(xv, q);
+    };
+    for (int e = wave; e < E; e += kRouteWaves) {
+        const float acc = router_logit<VEC>(load_x, rw + (size_t)e * d, d, lane);
         if (lane == 0) s_logit[e] = acc + (rb ? rb[e] : 0.f);
     }
     __syncthreads();
     if (wave != 0) return;
 
-    // lane e owns expert e; lanes >= E carry -inf and an index that never wins a tie
-    const bool valid = lane < E;
-    const float logit = valid ? s_logit[lane] : -INFINITY;
-    float cand = logit;  // -inf once taken
-    float vmax = 0.f;
-    float p_sel_sum = 0.f;
-    float my_p = 0.f;
-    int my_slot = -1;  // selection round in which this lane's expert was taken
-    for (int j = 0; j < k; ++j) {
-        float bv = cand;
-        int bi = lane;
-#pragma unroll
-        for (int m = 32; m >= 1; m >>= 1) {
-            float ov = __shfl_xor(bv, m, kWave);
-            int oi = __shfl_xor(bi, m, kWave);
-            if (ov > bv || (ov == bv && oi < bi)) {
-                bv = ov;
-                bi = oi;
-            }
-        }
-        if (j == 0) vmax = bv;  // the first pick is the row maximum
-        if (lane == bi) {
-            cand = -INFINITY;
-            my_slot = j;
-        }
-    }
-    my_p = valid ? __expf(logit - vmax) : 0.f;
-    const float den = wave_sum(my_p);
-    p_sel_sum = wave_sum(my_slot >= 0 ? my_p : 0.f);
-    if (probs && valid) probs[(size_t)t * E + lane] = my_p / den;
-    if (my_slot >= 0) {
-        topk_idx[(size_t)t * k + my_slot] = lane;
+    const RouterPick r = router_select(lane, E, k, lane < E ? s_logit[lane] : 0.f);
+    if (probs && lane < E) probs[(size_t)t * E + lane] = r.p / r.den;
+    if (r.slot >= 0) {
+        topk_idx[(size_t)t * k + r.slot] = lane;
         // (p/den) / (sum_sel p/den) with the common 1/den cancelled
-        topk_gate[(size_t)t * k + my_slot] = my_p / p_sel_sum;
+        topk_gate[(size_t)t * k + r.slot] = r.p / r.sel_sum;
     }
 }
 
