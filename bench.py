@@ -106,6 +106,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="phone_prefill", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run three 256 MiB device copies (a known-size kernel that scales the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0,
                     help="target wall time of the CPU oracle sample")
     args = ap.parse_args()
@@ -167,6 +170,14 @@ def main():
             pkg.moe_stack_forward(shape, ws_i, xs[i % n_inputs], y, None, ws)
         else:
             pkg.moe_forward(shape, ws_i[0], xs[i % n_inputs], y, None, None, ws)
+
+    if args.pmc_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for i in range(warmup):
         step(i)
