@@ -415,19 +415,41 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_deep_ker
         gload(r1, min(BK, k_last));
         lstore(0, r0);
         __syncthreads();
+        // Issue order inside a step: the step's global loads and LDS writes are spread through
+        // the MFMA sequence (one memory instruction in the shadow of each MFMA) instead of
+        // running as separate phases, so a wave's MFMA stream has no load/store-only gaps.
+        auto interleave = [&]() {
+#if defined(__HIP_DEVICE_COMPILE__)
+            constexpr int NM = MT * NT * (BK / 16);           // MFMAs per step
+            constexpr int NR = (MT * NA + NT) * (BK / 16);    // LDS fragment reads per step
+            constexpr int NL = AI * NA + BI;                  // global loads = LDS writes per step
+            constexpr int RPM = (NR + NM - 1) / NM;
+            constexpr int LPM = (2 * NL + NM - 1) / NM;
+            __builtin_amdgcn_sched_group_barrier(0x100, MT * NA + NT, 0);  // first fragments
+#pragma unroll
+            for (int i = 0; i < NM; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // one MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, RPM, 0);  // next fragments
+                if (i < NM / 2)
+                    __builtin_amdgcn_sched_group_barrier(0x020, LPM, 0);  // global loads, tile kt+2
+                else
+                    __builtin_amdgcn_sched_group_barrier(0x200, LPM, 0);  // LDS writes, tile kt+1
+            }
+#endif
+        };
         for (int kt = 0; kt < nk; kt += 2) {
             // even step: multiply tile kt (stage 0); r0 is free, r1 holds tile kt+1
             gload(r0, min((kt + 2) * BK, k_last));
             compute(0);
-            __builtin_amdgcn_sched_barrier(0);
             lstore(1, r1);
+            interleave();
             __syncthreads();
             if (kt + 1 >= nk) break;
             // odd step: multiply tile kt+1 (stage 1); r1 is free, r0 holds tile kt+2
             gload(r1, min((kt + 3) * BK, k_last));
             compute(1);
-            __builtin_amdgcn_sched_barrier(0);
             lstore(0, r0);
+            interleave();
             __syncthreads();
         }
     }
@@ -574,9 +596,12 @@ static int run_gemm(const moe_shape& s, GemmArgs& g, bool swiglu, hipStream_t st
         fast &= g.seg[i].K % 64 == 0;  // the deep pipeline has no K tail
     }
     if (fast) {
+        // Measured on the phone shape with Zipf-skewed groups: the wide gate/up product (N = 2F)
+        // is fastest with 128 x 256 tiles (64 x 128 per wave); the down projection (N = d) needs
+        // the smaller 128 x 128 tile to have enough workgroups for 256 CUs.
         if (swiglu)
-            return dual ? launch_bf16_deep<128, 128, 64, 64, 64, true, true>(g, st)
-                        : launch_bf16_deep<128, 128, 64, 64, 64, true, false>(g, st);
+            return dual ? launch_bf16_deep<128, 256, 64, 64, 128, true, true>(g, st)
+                        : launch_bf16_deep<128, 256, 64, 64, 128, true, false>(g, st);
         return launch_bf16_deep<128, 128, 64, 64, 64, false, false>(g, st);
     }
     if (swiglu)
