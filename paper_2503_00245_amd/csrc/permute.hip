@@ -83,29 +83,75 @@ __device__ void scatter_chunk(const int32_t* __restrict__ keys, int p0, int p1, 
     }
 }
 
-// ---- single-workgroup path: histogram + scan + scatter --------------------------------
+// ---- single-workgroup path (P <= kChunk): keys stay in registers ---------------------------
+// Pass q covers pairs [q*1024, (q+1)*1024).  One sweep gives every pair its in-wave rank and
+// every (pass, wave, expert) its count; a wave-level scan per expert over the 128 (pass, wave)
+// cells turns counts into bases, a 64-lane scan of the expert totals gives the offsets, and
+// slot = offset[e] + base[pass][wave][e] + rank.  Three barriers in all.
+constexpr int kSmallPasses = kChunk / kSortThreads;
+
+__device__ __forceinline__ int wave_inclusive_scan(int v, int lane) {
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const int o = __shfl_up(v, d, kWave);
+        if (lane >= d) v += o;
+    }
+    return v;
+}
+
 __global__ __launch_bounds__(kSortThreads) void permute_small_kernel(
     const int32_t* __restrict__ keys, int P, int E, int32_t* __restrict__ offsets,
     int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm) {
-    __shared__ int s_hist[kMaxExperts];
-    __shared__ int s_run[kMaxExperts];
-    __shared__ int s_wcount[kSortWaves][kMaxExperts];
-    if (threadIdx.x < kMaxExperts) s_hist[threadIdx.x] = 0;
+    __shared__ int s_cnt[kSmallPasses * kSortWaves][kMaxExperts];  // [pass*16 + wave][expert]
+    __shared__ int s_total[kMaxExperts];
+    __shared__ int s_off[kMaxExperts];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int npass = (P + kSortThreads - 1) / kSortThreads;
+    constexpr int kCells = kSmallPasses * kSortWaves;  // 128 = two per lane
+
+    for (int i = threadIdx.x; i < kCells * kMaxExperts; i += kSortThreads) (&s_cnt[0][0])[i] = 0;
     __syncthreads();
-    for (int q = 0; q < P; q += kSortThreads)
-        wave_hist(load_key(keys, q + threadIdx.x, P, E), threadIdx.x & (kWave - 1), s_hist);
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        int acc = 0;
-        for (int e = 0; e < E; ++e) {
-            s_run[e] = acc;
-            offsets[e] = acc;
-            acc += s_hist[e];
+    int key[kSmallPasses], rank[kSmallPasses];
+#pragma unroll
+    for (int q = 0; q < kSmallPasses; ++q) {
+        key[q] = -1;
+        rank[q] = 0;
+        if (q < npass) {
+            key[q] = load_key(keys, q * kSortThreads + threadIdx.x, P, E);
+            rank[q] = wave_rank(key[q], lane, s_cnt[q * kSortWaves + wave]);
         }
-        offsets[E] = acc;
     }
     __syncthreads();
-    scatter_chunk(keys, 0, P, E, s_run, s_wcount, perm, inv_perm);
+    for (int e = wave; e < E; e += kSortWaves) {
+        const int v0 = s_cnt[lane][e], v1 = s_cnt[lane + kWave][e];
+        const int i0 = wave_inclusive_scan(v0, lane);
+        const int t0 = __shfl(i0, kWave - 1, kWave);
+        const int i1 = wave_inclusive_scan(v1, lane) + t0;
+        s_cnt[lane][e] = i0 - v0;
+        s_cnt[lane + kWave][e] = i1 - v1;
+        if (lane == kWave - 1) s_total[e] = i1;
+    }
+    __syncthreads();
+    if (wave == 0) {
+        const int tot = lane < E ? s_total[lane] : 0;
+        const int excl = wave_inclusive_scan(tot, lane) - tot;
+        if (lane < E) {
+            s_off[lane] = excl;
+            offsets[lane] = excl;
+        }
+        if (lane == E - 1) offsets[E] = excl + tot;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < kSmallPasses; ++q) {
+        if (key[q] >= 0) {
+            const int p = q * kSortThreads + threadIdx.x;
+            const int slot = s_off[key[q]] + s_cnt[q * kSortWaves + wave][key[q]] + rank[q];
+            perm[slot] = p;
+            inv_perm[p] = slot;
+        }
+    }
 }
 
 // ---- multi-workgroup path ---------------------------------------------------------------------

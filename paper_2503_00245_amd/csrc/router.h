@@ -1,34 +1,43 @@
-// Router arithmetic shared by the stand-alone route kernel and the single-token expert
-// kernel that recomputes the routing in its prologue (Sec. 2.3: Eq. 2 softmax at
-// temperature 1, Eq. 3 top-k; lowest index wins ties; gates renormalised over the k
-// chosen).  Both callers go through these functions with the same lane layout, so their
-// logits, indices and gates are bit-identical.
+// Router arithmetic (Sec. 2.3: Eq. 2 softmax at temperature 1, Eq. 3 top-k; lowest index
+// wins ties; gates renormalised over the k chosen), kept apart from the kernel that drives
+// it so that every caller produces bit-identical logits, indices and gates.
 #pragma once
 
 #include "common.h"
 
 namespace moe {
 
-// One wave: logit <x, we> (+ nothing: the caller adds the bias).  Lane l takes elements
-// [l*VEC, l*VEC+VEC) of every 64*VEC-wide chunk, fused multiply-adds in ascending index
-// order, then a 64-lane butterfly.  load_x(i, out) must yield x[i .. i+VEC) as floats.
-template <int VEC, typename LoadX>
-__device__ __forceinline__ float router_logit(LoadX load_x, const float* __restrict__ we, int d,
-                                              int lane) {
-    float acc = 0.f;
-    for (int i = lane * VEC; i < d; i += kWave * VEC) {
-        float xv[VEC];
-        load_x(i, xv);
+// One wave, TOK tokens at once: logits <x_t, we> (the caller adds the bias).  Lane l takes
+// elements [l*VEC, l*VEC+VEC) of every 64*VEC-wide chunk; per token the fused multiply-adds
+// run in ascending index order and end in a 64-lane butterfly, so a token's logit does not
+// depend on TOK.  load_x(t, i, out) must yield x_t[i .. i+VEC) as floats; tokens t >= ntok
+// are skipped.  The router row is read once per chunk and reused for all TOK tokens.
+template <int VEC, int TOK, typename LoadX>
+__device__ __forceinline__ void router_logits(LoadX load_x, const float* __restrict__ we, int d,
+                                              int lane, int ntok, float (&out)[TOK]) {
+    float acc[TOK];
 #pragma unroll
-        for (int q = 0; q < VEC; q += 4) {
-            const f32x4 wv = *reinterpret_cast<const f32x4*>(we + i + q);
-            acc = fmaf(xv[q + 0], wv[0], acc);
-            acc = fmaf(xv[q + 1], wv[1], acc);
-            acc = fmaf(xv[q + 2], wv[2], acc);
-            acc = fmaf(xv[q + 3], wv[3], acc);
+    for (int t = 0; t < TOK; ++t) acc[t] = 0.f;
+    for (int i = lane * VEC; i < d; i += kWave * VEC) {
+        f32x4 wv[VEC / 4];
+#pragma unroll
+        for (int q = 0; q < VEC; q += 4) wv[q / 4] = *reinterpret_cast<const f32x4*>(we + i + q);
+#pragma unroll
+        for (int t = 0; t < TOK; ++t) {
+            if (t >= ntok) continue;
+            float xv[VEC];
+            load_x(t, i, xv);
+#pragma unroll
+            for (int q = 0; q < VEC; q += 4) {
+                acc[t] = fmaf(xv[q + 0], wv[q / 4][0], acc[t]);
+                acc[t] = fmaf(xv[q + 1], wv[q / 4][1], acc[t]);
+                acc[t] = fmaf(xv[q + 2], wv[q / 4][2], acc[t]);
+                acc[t] = fmaf(xv[q + 3], wv[q / 4][3], acc[t]);
+            }
         }
     }
-    return wave_sum(acc);
+#pragma unroll
+    for (int t = 0; t < TOK; ++t) out[t] = wave_sum(acc[t]);
 }
 
 struct RouterPick {
