@@ -182,6 +182,41 @@ MOE_API int moe_forward_timed(const moe_shape* shape, const moe_weights* weights
                               void* y, void* workspace, size_t workspace_bytes, void* stream,
                               float* stage_ms, const char** stage_names, int32_t* n_stages);
 
+/*
+ * Hard expert replacements of a routing trace (Sec. 2.3, Eq. 4): S [B,T,K] int32 holds the
+ * experts selected for token t of sequence b (for example topk_idx of moe_route, or the
+ * topk_trace of moe_stack_forward with B = layers).
+ *   H_e[e] = sum_b sum_{t<T-1} | [e in S[b,t+1]] - [e in S[b,t]] |,   H = sum_e H_e.
+ * Every replacement is counted twice; Eq. 5 uses floor(H/2).  H_e [E] and H [1] are int64
+ * device outputs.  1 <= K <= E <= 64.
+ */
+MOE_API int moe_expert_replacements(const int32_t* S, int32_t B, int32_t T, int32_t K, int32_t E,
+                                    int64_t* H_e, int64_t* H, void* stream);
+
+/*
+ * Forward value of the block-wise expert selection loss (Sec. 2.3, Eq. 4-7) from the routing
+ * probabilities probs [B,T,E] fp32 (the optional output of moe_route) and the selection S [B,T,K]:
+ *   H_norm = floor(H/2) / (B K (T-1)),  L = sum |W[b,t+1,e] - W[b,t,e]|,  L_norm = L / (B T),
+ *   loss = H_norm * L_norm.
+ * out [5] fp64 device: H, H_norm, L, L_norm, loss.  The backward pass is not provided.
+ * workspace: moe_bles_workspace_bytes(B, T, E) device bytes.
+ */
+MOE_API size_t moe_bles_workspace_bytes(int32_t B, int32_t T, int32_t E);
+MOE_API int moe_bles_loss(const float* probs, const int32_t* S, int32_t B, int32_t T, int32_t K,
+                          int32_t E, double* out, void* workspace, size_t workspace_bytes,
+                          void* stream);
+
+/*
+ * Counters of the expert-offloading rule (Sec. 3.4.2): for each layer l of trace [L,T,K], whenever
+ * the selected set differs from the previous token's, the non-selected experts leave the GPU
+ * and the selected ones are brought in.  changes[l] = number of tokens whose set differs from
+ * the previous one (the first token differs from the empty set); loads[l] = experts brought
+ * in = sum_t |S_t \ S_{t-1}|.  Multiply loads by the bytes of one expert for the traffic the
+ * rule would cause.  changes, loads: [L] int64 device outputs.
+ */
+MOE_API int moe_offload_counters(const int32_t* trace, int32_t L, int32_t T, int32_t K, int32_t E,
+                                 int64_t* changes, int64_t* loads, void* stream);
+
 /* Bytes of workspace that any entry point above needs for this shape (0 if invalid). */
 MOE_API size_t moe_workspace_bytes(const moe_shape* shape);
 

@@ -28,6 +28,8 @@
  *   oracle_stack_forward  x_{l+1} = x_l + layer_l(x_l) (benchmark construct, not
  *                       in the paper: no attention, no normalisation).
  *   oracle_expert_replacements  Sec. 2.3 Eq. 4 (H_e, H) and the floor(H/2) of Eq. 5.
+ *   oracle_bles_loss    Sec. 2.3 Eq. 4-7, the forward value of the block-wise expert selection loss.
+ *   oracle_offload_counters  Sec. 3.4.2: set changes and expert loads under the offloading rule.
  *
  * Parity pins (tests/test_oracle_*.py): closed forms, library routines on
  * special cases, brute force on tiny inputs and the worked example of Fig. 5.
@@ -344,4 +346,67 @@ int oracle_num_threads(void) {
 #else
     return 1;
 #endif
+}
+
+/*
+ * Block-wise expert selection loss, forward value only (Sec. 2.3):
+ *   Eq. 4   H   = sum_e sum_b sum_{t<T-1} | [e in S[b,t+1]] - [e in S[b,t]] |
+ *   Eq. 5   H_norm = floor(H/2) / (B K (T-1))
+ *   Eq. 6   L   = sum_b sum_{t<T-1} sum_e | W[b,t+1,e] - W[b,t,e] |,  L_norm = L / (B T)
+ *   Eq. 7   loss = H_norm * L_norm
+ * W [B,T,E] routing probabilities (fp32 storage, widened), S [B,T,K] selected experts.
+ * out[0..4] = H, H_norm, L, L_norm, loss.  T == 1 gives H_norm = 0 (no adjacent pair).
+ */
+int oracle_bles_loss(int B, int T, int K, int E, const float* W, const int32_t* S, double* out) {
+    if (B < 1 || T < 1 || K < 1 || E < 1) return -1;
+    int64_t H = oracle_expert_replacements(B, T, K, E, S, NULL);
+    double L = 0.0;
+    for (int b = 0; b < B; ++b)
+        for (int t = 0; t + 1 < T; ++t)
+            for (int e = 0; e < E; ++e) {
+                double d = (double)W[((size_t)b * T + t + 1) * E + e] - (double)W[((size_t)b * T + t) * E + e];
+                L += d < 0 ? -d : d;
+            }
+    double Hn = T > 1 ? (double)(H / 2) / ((double)B * K * (T - 1)) : 0.0;
+    double Ln = L / ((double)B * T);
+    out[0] = (double)H;
+    out[1] = Hn;
+    out[2] = L;
+    out[3] = Ln;
+    out[4] = Hn * Ln;
+    return 0;
+}
+
+/*
+ * Expert-residency counters of the offloading rule (Sec. 3.4.2, Eq. "offload"): for every
+ * layer l and token t, if the selected set S differs from S_prev, every non-selected expert
+ * goes to the CPU and every selected one to the GPU, and S_prev <- S.  With at most K experts
+ * resident, the experts that must be brought in at a change are S \ S_prev.
+ * trace [L,T,K]; S_prev starts empty, so the first token of a layer loads its K experts.
+ *   changes[l] = #{t : set(S_t) != set(S_{t-1})}   (t = 0 counts: the empty set differs)
+ *   loads[l]   = sum_t |S_t \ S_{t-1}|
+ */
+int oracle_offload_counters(int L, int T, int K, int E, const int32_t* trace, int64_t* changes,
+                            int64_t* loads) {
+    if (E > 64) return -1;
+    for (int l = 0; l < L; ++l) {
+        uint64_t prev = 0;
+        int64_t ch = 0, ld = 0;
+        for (int t = 0; t < T; ++t) {
+            uint64_t cur = 0;
+            for (int j = 0; j < K; ++j) cur |= (uint64_t)1 << trace[((size_t)l * T + t) * K + j];
+            if (cur != prev) {
+                ch += 1;
+                uint64_t in = cur & ~prev;
+                while (in) {
+                    ld += 1;
+                    in &= in - 1;
+                }
+                prev = cur;
+            }
+        }
+        changes[l] = ch;
+        loads[l] = ld;
+    }
+    return 0;
 }

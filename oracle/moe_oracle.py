@@ -193,3 +193,28 @@ def expert_replacements(S, n_experts: int):
     He = np.zeros(n_experts, np.int64)
     H = lib().oracle_expert_replacements(B, T, K, n_experts, _p(S), _p(He))
     return int(H), He
+
+
+def bles_loss(probs, S):
+    """Eq. 4-7 forward value: dict(H, H_norm, L, L_norm, loss) for probs f32 [B,T,E], S int32 [B,T,K]."""
+    W = _c(probs, np.float32)
+    S = _c(S, np.int32)
+    B, T, E = W.shape
+    K = S.shape[2]
+    out = np.zeros(5, np.float64)
+    rc = lib().oracle_bles_loss(B, T, K, E, _p(W), _p(S), _p(out))
+    if rc != 0:
+        raise ValueError(f"oracle_bles_loss rejected its arguments (rc={rc})")
+    return dict(H=int(out[0]), H_norm=out[1], L=out[2], L_norm=out[3], loss=out[4])
+
+
+def offload_counters(trace, n_experts: int):
+    """Sec. 3.4.2 offloading rule on a routing trace int32 [L,T,K] -> (changes int64 [L], loads int64 [L])."""
+    tr = _c(trace, np.int32)
+    L, T, K = tr.shape
+    ch = np.zeros(L, np.int64)
+    ld = np.zeros(L, np.int64)
+    rc = lib().oracle_offload_counters(L, T, K, n_experts, _p(tr), _p(ch), _p(ld))
+    if rc != 0:
+        raise ValueError(f"oracle_offload_counters rejected its arguments (rc={rc})")
+    return ch, ld

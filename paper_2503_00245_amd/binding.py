@@ -20,7 +20,9 @@ FLAG_SHARED_BASE, FLAG_RESIDUAL = 1, 2
 WEIGHT_FIELDS = ("router_w", "router_b", "w_gate", "w_up", "w_down",
                  "rg", "ru", "rd", "lg", "lu", "ld")
 EXPORTS = ("moe_route", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_forward",
-           "moe_stack_forward", "moe_forward_timed", "moe_workspace_bytes", "moe_status_string")
+           "moe_stack_forward", "moe_forward_timed", "moe_workspace_bytes", "moe_status_string",
+           "moe_expert_replacements", "moe_bles_workspace_bytes", "moe_bles_loss",
+           "moe_offload_counters")
 
 
 class MoeShape(C.Structure):
@@ -64,8 +66,15 @@ def lib() -> C.CDLL:
         L.moe_stack_forward.argtypes = [sp, wp, C.c_int32, vp, vp, vp, vp, sz, vp]
         L.moe_forward_timed.argtypes = [sp, wp, vp, vp, vp, sz, vp, C.POINTER(C.c_float),
                                         C.POINTER(C.c_char_p), C.POINTER(C.c_int32)]
+        i32 = C.c_int32
+        L.moe_expert_replacements.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp]
+        L.moe_bles_workspace_bytes.argtypes = [i32, i32, i32]
+        L.moe_bles_workspace_bytes.restype = C.c_size_t
+        L.moe_bles_loss.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, sz, vp]
+        L.moe_offload_counters.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp]
         for fn in ("moe_route", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_forward",
-                   "moe_stack_forward", "moe_forward_timed"):
+                   "moe_stack_forward", "moe_forward_timed", "moe_expert_replacements",
+                   "moe_bles_loss", "moe_offload_counters"):
             getattr(L, fn).restype = C.c_int
         _lib = L
     return _lib
@@ -192,3 +201,30 @@ def moe_forward_timed(shape: MoeShape, weights: MoeWeights, x, y, workspace):
         C.byref(shape), C.byref(weights), _ptr(x), _ptr(y), _ptr(workspace), workspace.numel(),
         _stream(y.device), ms, names, C.byref(n)))
     return [(names[i].decode(), float(ms[i])) for i in range(n.value)]
+
+
+def moe_expert_replacements(S, n_experts: int, H_e, H) -> None:
+    """S int32 [B,T,K] device; H_e int64 [E], H int64 [1] device outputs."""
+    B, T, K = S.shape
+    _check("moe_expert_replacements", lib().moe_expert_replacements(
+        _ptr(S), B, T, K, n_experts, _ptr(H_e), _ptr(H), _stream(S.device)))
+
+
+def moe_bles_workspace_bytes(B: int, T: int, E: int) -> int:
+    return int(lib().moe_bles_workspace_bytes(B, T, E))
+
+
+def moe_bles_loss(probs, S, out, workspace) -> None:
+    """probs f32 [B,T,E], S int32 [B,T,K]; out f64 [5] device: H, H_norm, L, L_norm, loss."""
+    B, T, E = probs.shape
+    K = S.shape[2]
+    _check("moe_bles_loss", lib().moe_bles_loss(
+        _ptr(probs), _ptr(S), B, T, K, E, _ptr(out), _ptr(workspace), workspace.numel(),
+        _stream(probs.device)))
+
+
+def moe_offload_counters(trace, n_experts: int, changes, loads) -> None:
+    """trace int32 [L,T,K]; changes, loads int64 [L] device outputs."""
+    L_, T, K = trace.shape
+    _check("moe_offload_counters", lib().moe_offload_counters(
+        _ptr(trace), L_, T, K, n_experts, _ptr(changes), _ptr(loads), _stream(trace.device)))

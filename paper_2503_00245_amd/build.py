@@ -12,7 +12,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmoe_mi355x.so")
-SOURCES = ["api.hip", "route.hip", "permute.hip", "combine.hip", "expert_gemv.hip", "expert_gemm.hip"]
+SOURCES = ["api.hip", "route.hip", "permute.hip", "combine.hip", "expert_gemv.hip", "expert_gemm.hip",
+           "metrics.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-command-line-argument",
@@ -38,7 +39,7 @@ def _compile(src):
 
 def build(verbose: bool = False) -> str:
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=6) as ex:
+    with ThreadPoolExecutor(max_workers=7) as ex:
         results = list(ex.map(_compile, SOURCES))
     if verbose:
         for _, err in results:

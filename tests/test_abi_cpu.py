@@ -18,7 +18,7 @@ def _declared():
 
 def test_library_exports_every_declared_symbol():
     names = _declared()
-    assert set(names) == set(pkg.EXPORTS) and len(names) == 9
+    assert set(names) == set(pkg.EXPORTS) and len(names) == 13
     L = pkg.lib()
     for n in names:
         assert getattr(L, n) is not None
@@ -97,3 +97,17 @@ def test_zero_tokens_is_a_no_op_without_touching_pointers():
         setattr(w, n, 4096)
     assert L.moe_forward(C.byref(shape), C.byref(w), None, None, None, None, None, 0, None) == 0
     assert L.moe_expert_ffn(C.byref(shape), C.byref(w), None, None, None, None, 0, None) == 0
+
+
+def test_trace_metric_entry_points_reject_bad_shapes_on_the_host():
+    L = pkg.lib()
+    ok = C.c_void_p(4096)
+    assert L.moe_expert_replacements(ok, 1, 8, 3, 2, ok, ok, None) == -1      # K > E
+    assert L.moe_expert_replacements(ok, 1, 8, 2, 65, ok, ok, None) == -2     # E > 64
+    assert L.moe_expert_replacements(None, 1, 8, 2, 8, ok, ok, None) == -1
+    assert L.moe_offload_counters(ok, 0, 8, 2, 8, ok, ok, None) == -1
+    assert L.moe_offload_counters(ok, 2, 8, 2, 8, None, ok, None) == -1
+    assert pkg.moe_bles_workspace_bytes(4, 128, 8) >= 8 * 65 + 4 * (4 * 127 * 8 // 256)
+    assert pkg.moe_bles_workspace_bytes(4, 128, 65) == 0
+    assert L.moe_bles_loss(ok, ok, 4, 128, 2, 8, ok, ok, 16, None) == -3       # short workspace
+    assert L.moe_bles_loss(ok, ok, 4, 128, 2, 8, None, ok, 1 << 20, None) == -1

@@ -372,3 +372,155 @@ def test_stack_small(dev, oracle):
 
 def test_stack_phone_width_decode(dev, oracle):
     _stack_case(dev, oracle, wl.CONFIGS["phone_stack"], 3, 1)
+
+
+# ------------------------------------------------------------------------------- routing-trace metrics
+
+def _fig5_trace(name):
+    import os
+    m = np.loadtxt(os.path.join(os.path.dirname(__file__), "golden", name), dtype=np.int64, comments="#")
+    return np.stack([np.flatnonzero(m[:, t]) for t in range(m.shape[1])]).astype(np.int32)[None]
+
+
+def _random_trace(seed, B, T, K, E, sticky=0.7):
+    """Selections that change only now and then, like a router with temporal locality."""
+    rng = np.random.default_rng(seed)
+    S = np.zeros((B, T, K), np.int32)
+    for b in range(B):
+        cur = rng.permutation(E)[:K]
+        for t in range(T):
+            if rng.random() > sticky:
+                cur = cur.copy()
+                cur[rng.integers(K)] = rng.choice(np.setdiff1d(np.arange(E), cur)) if E > K else cur[0]
+            S[b, t] = rng.permutation(cur)
+    return S
+
+
+@pytest.mark.parametrize("case", ["fig5_bles", "fig5_moe", "random", "single_token", "wide", "long"])
+def test_expert_replacements_match_oracle_bit_exact(dev, oracle, case):
+    if case.startswith("fig5"):
+        S, E = _fig5_trace(case + ".txt"), 8
+    elif case == "random":
+        S, E = _random_trace(1, 5, 333, 2, 8), 8
+    elif case == "single_token":
+        S, E = _random_trace(2, 4, 1, 2, 8), 8
+    elif case == "wide":
+        S, E = _random_trace(3, 2, 700, 8, 64, sticky=0.3), 64
+    else:
+        S, E = _random_trace(4, 24, 4096, 2, 8), 8
+    He = torch.full((E,), -1, dtype=torch.int64, device=dev)
+    H = torch.full((1,), -1, dtype=torch.int64, device=dev)
+    pkg.moe_expert_replacements(to_device(S, dev), E, He, H)
+    torch.cuda.synchronize()
+    rH, rHe = oracle.expert_replacements(S, E)
+    assert int(H.item()) == rH and np.array_equal(He.cpu().numpy(), rHe)
+    if case == "fig5_bles":
+        assert rH // 2 == 11
+    if case == "fig5_moe":
+        assert rH // 2 == 21
+
+
+@pytest.mark.parametrize("B,T,K,E", [(1, 2, 1, 2), (3, 257, 2, 8), (2, 2048, 2, 8), (1, 1, 2, 4), (4, 100, 8, 64)])
+def test_bles_loss_value_matches_oracle(dev, oracle, B, T, K, E):
+    rng = np.random.default_rng(B * 1000 + T)
+    W = rng.random((B, T, E)).astype(np.float32) ** 3
+    W /= W.sum(-1, keepdims=True)
+    S = np.argsort(-W, axis=-1, kind="stable")[..., :K].astype(np.int32)
+    out = torch.full((5,), float("nan"), dtype=torch.float64, device=dev)
+    ws = torch.empty(pkg.moe_bles_workspace_bytes(B, T, E), dtype=torch.uint8, device=dev)
+    pkg.moe_bles_loss(to_device(W, dev), to_device(S, dev), out, ws)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    ref = oracle.bles_loss(W, S)
+    assert got[0] == ref["H"] and got[1] == ref["H_norm"]          # integer part exact
+    for i, key in ((2, "L"), (3, "L_norm"), (4, "loss")):            # fp32 block sums, fp64 total
+        assert abs(got[i] - ref[key]) <= 2e-6 * max(abs(ref[key]), 1e-30), (key, got[i], ref[key])
+
+
+def test_bles_loss_from_the_routers_own_probabilities(dev, oracle):
+    cfg = _cfg(d=256, E=8, k=2, dtype="bf16", seed=77, std=0.3)
+    w_np = wl.make_layer_weights(cfg, with_bias=False)
+    B, T = 3, 200
+    x_np = wl.make_inputs(cfg, B * T)
+    w_t = weights_to_device({"router_w": w_np["router_w"], "router_b": None}, dev)
+    idx, gate, probs = _route_gpu(dev, to_device(x_np, dev), w_t, 8, 2, pkg.MOE_BF16)
+    probs_t = to_device(probs.astype(np.float32).reshape(B, T, 8), dev)
+    S_t = to_device(idx.reshape(B, T, 2), dev)
+    out = torch.zeros(5, dtype=torch.float64, device=dev)
+    ws = torch.empty(pkg.moe_bles_workspace_bytes(B, T, 8), dtype=torch.uint8, device=dev)
+    pkg.moe_bles_loss(probs_t, S_t, out, ws)
+    torch.cuda.synchronize()
+    ref = oracle.bles_loss(probs.astype(np.float32).reshape(B, T, 8), idx.reshape(B, T, 2))
+    got = out.cpu().numpy()
+    assert got[0] == ref["H"] and abs(got[4] - ref["loss"]) <= 2e-6 * ref["loss"]
+    assert 0.0 < ref["loss"] < 2.0
+
+
+@pytest.mark.parametrize("L,T,K,E", [(1, 35, 2, 8), (24, 256, 2, 8), (3, 1, 2, 4), (2, 1000, 4, 16), (5, 300, 8, 64)])
+def test_offload_counters_match_oracle_bit_exact(dev, oracle, L, T, K, E):
+    tr = _fig5_trace("fig5_moe.txt") if (L, T) == (1, 35) else _random_trace(L + T, L, T, K, E, sticky=0.6)
+    ch = torch.full((L,), -1, dtype=torch.int64, device=dev)
+    ld = torch.full((L,), -1, dtype=torch.int64, device=dev)
+    pkg.moe_offload_counters(to_device(tr, dev), E, ch, ld)
+    torch.cuda.synchronize()
+    rch, rld = oracle.offload_counters(tr, E)
+    assert np.array_equal(ch.cpu().numpy(), rch) and np.array_equal(ld.cpu().numpy(), rld)
+    if (L, T) == (1, 35):
+        assert rld[0] == 2 + 21  # the paper's 21 replacements after the initial fill
+
+
+def test_stack_trace_feeds_the_trace_metrics(dev, oracle):
+    cfg = wl.shrink(wl.CONFIGS["phone_stack"], d_model=256, d_ff=512, weight_std=0.05)
+    n_layers, T = 6, 64
+    layers_np = wl.make_stack_weights(cfg, n_layers)
+    layers_t = [weights_to_device(w, dev) for w in layers_np]
+    shape = pkg.shape_for(layers_t[0], T, cfg.top_k, pkg.MOE_BF16)
+    ws = pkg.alloc_workspace(shape, dev)
+    x_t = to_device(wl.make_inputs(cfg, T), dev)
+    y = torch.empty_like(x_t)
+    trace = torch.empty((n_layers, T, cfg.top_k), dtype=torch.int32, device=dev)
+    pkg.moe_stack_forward(shape, [pkg.make_weights(w) for w in layers_t], x_t, y, trace, ws)
+    ch = torch.empty(n_layers, dtype=torch.int64, device=dev)
+    ld = torch.empty(n_layers, dtype=torch.int64, device=dev)
+    He = torch.empty(cfg.n_experts, dtype=torch.int64, device=dev)
+    H = torch.empty(1, dtype=torch.int64, device=dev)
+    pkg.moe_offload_counters(trace, cfg.n_experts, ch, ld)
+    pkg.moe_expert_replacements(trace, cfg.n_experts, He, H)
+    torch.cuda.synchronize()
+    tr = trace.cpu().numpy()
+    rch, rld = oracle.offload_counters(tr, cfg.n_experts)
+    rH, rHe = oracle.expert_replacements(tr, cfg.n_experts)
+    assert np.array_equal(ch.cpu().numpy(), rch) and np.array_equal(ld.cpu().numpy(), rld)
+    assert int(H.item()) == rH and np.array_equal(He.cpu().numpy(), rHe)
+    # loads after the initial fill of k experts per layer are exactly the replacements
+    assert int(rld.sum()) - n_layers * cfg.top_k == rH // 2
+
+
+# ------------------------------------------------------------------------------- the paper's own shapes
+
+@pytest.mark.parametrize("d,F,r", [
+    (1440, 3840, 0),     # phone-sized MoE row of Table 1 (hidden 1440, F = 8h/3)
+    (432, 1152, 0),      # wearable-sized MoE row (hidden 432)
+    (1600, 4264, 800),   # phone-sized WD row: hidden 1600, rank = hidden / 2
+    (400, 1064, 200),    # wearable-sized WD row
+])
+def test_forward_table1_shapes(dev, oracle, d, F, r):
+    # widths that are not multiples of the GEMM's K tile exercise the zero-filled-tail kernel
+    cfg = _cfg(name=f"t1_{d}", d=d, F=F, E=8, k=2, dtype="bf16", seed=600 + d, r=r, std=0.03)
+    w_np = wl.make_layer_weights(cfg, with_bias=False)
+    w_t = weights_to_device(w_np, dev)
+    _forward_case(dev, oracle, cfg, 1, w_np, w_t)
+    _forward_case(dev, oracle, cfg, 150, w_np, w_t, sample=24)
+
+
+@pytest.mark.parametrize("E", [2, 4, 8, 16])
+@pytest.mark.parametrize("k", [1, 2, 4, 8])
+def test_forward_active_and_total_expert_grid(dev, oracle, k, E):
+    # the ablation grid of Sec. 3.5 (k active of 8 total; 2 active of E total), at a small width
+    if k > E:
+        pytest.skip("k cannot exceed E")
+    cfg = _cfg(name=f"g{k}_{E}", d=256, F=384, E=E, k=k, dtype="bf16", seed=700 + 10 * k + E, std=0.05)
+    w_np = wl.make_layer_weights(cfg, with_bias=False)
+    w_t = weights_to_device(w_np, dev)
+    _forward_case(dev, oracle, cfg, 1, w_np, w_t)
+    _forward_case(dev, oracle, cfg, 70, w_np, w_t)

@@ -423,3 +423,94 @@ def test_expert_replacements_closed_forms(oracle):
     assert H == 9 * 4 and np.all(He == 9)
     two = np.concatenate([const, const], axis=0)  # batches do not interact
     assert oracle.expert_replacements(two, 8)[0] == 0
+
+
+# ----------------------------------------------------------------- BlES loss value (Eq. 4-7)
+
+def _fig5_selection(name):
+    m = _load_indicator(name)
+    return np.stack([np.flatnonzero(m[:, t]) for t in range(35)]).astype(np.int32)[None]
+
+
+def test_bles_loss_closed_forms(oracle):
+    # constant routing and constant probabilities: no replacements, zero loss
+    S = np.tile(np.array([[1, 3]], np.int32), (2, 6, 1))
+    W = np.tile(np.array([0.1, 0.4, 0.1, 0.4], np.float32), (2, 6, 1))
+    r = oracle.bles_loss(W, S)
+    assert r["H"] == 0 and r["L"] == 0.0 and r["loss"] == 0.0
+    # two tokens, one batch: L is the L1 distance of the two probability rows, L_norm = L / 2
+    W2 = np.array([[[0.5, 0.25, 0.25, 0.0], [0.0, 0.25, 0.25, 0.5]]], np.float32)
+    S2 = np.array([[[0, 1], [3, 1]]], np.int32)  # one expert replaced: H = 2, floor(H/2) = 1
+    r = oracle.bles_loss(W2, S2)
+    assert r["H"] == 2 and r["H_norm"] == 1.0 / (1 * 2 * 1)
+    assert r["L"] == 1.0 and r["L_norm"] == 0.5 and r["loss"] == 0.25
+    # probabilities alternating between two one-hot rows: each step contributes 2 to L
+    T = 9
+    Wa = np.zeros((3, T, 5), np.float32)
+    Wa[:, 0::2, 0] = 1.0
+    Wa[:, 1::2, 4] = 1.0
+    Sa = np.zeros((3, T, 1), np.int32)
+    Sa[:, 1::2, 0] = 4
+    r = oracle.bles_loss(Wa, Sa)
+    assert r["L"] == 3 * (T - 1) * 2.0 and r["L_norm"] == r["L"] / (3 * T)
+    assert r["H"] == 3 * (T - 1) * 2 and r["H_norm"] == 1.0  # every step replaces the one expert
+    # a single token has no adjacent pair
+    assert oracle.bles_loss(Wa[:, :1], Sa[:, :1])["loss"] == 0.0
+
+
+@pytest.mark.parametrize("name,replacements", [("fig5_bles.txt", 11), ("fig5_moe.txt", 21)])
+def test_bles_hard_term_on_the_papers_worked_example(oracle, name, replacements):
+    S = _fig5_selection(name)
+    W = np.full((1, 35, 8), 0.125, np.float32)
+    r = oracle.bles_loss(W, S)
+    assert r["H_norm"] == replacements / (1 * 2 * 34)  # Eq. 5 with B = 1, K = 2, T = 35
+    assert r["L"] == 0.0
+
+
+def test_bles_soft_term_matches_library_reduction(oracle):
+    rng = np.random.default_rng(7)
+    W = rng.random((4, 33, 8)).astype(np.float32)
+    W /= W.sum(-1, keepdims=True)
+    S = np.argsort(-W, axis=-1)[..., :2].astype(np.int32)
+    r = oracle.bles_loss(W, S)
+    ref = np.abs(np.diff(W.astype(np.float64), axis=1)).sum()
+    assert np.isclose(r["L"], ref, rtol=1e-13) and np.isclose(r["L_norm"], ref / (4 * 33), rtol=1e-13)
+    H, _ = oracle.expert_replacements(S, 8)
+    assert r["H"] == H and np.isclose(r["loss"], (H // 2) / (4 * 2 * 32) * ref / (4 * 33), rtol=1e-13)
+
+
+# ----------------------------------------------------------------- offloading rule counters (Sec. 3.4.2)
+
+@pytest.mark.parametrize("name,replacements", [("fig5_bles.txt", 11), ("fig5_moe.txt", 21)])
+def test_offload_counters_on_the_papers_worked_example(oracle, name, replacements):
+    S = _fig5_selection(name)  # [1, 35, 2] = one layer's trace
+    changes, loads = oracle.offload_counters(S, 8)
+    # the first token fills the two resident slots; every later load is one replacement
+    assert loads[0] == 2 + replacements
+    m = _load_indicator(name)
+    assert changes[0] == 1 + int((np.abs(np.diff(m, axis=1)).sum(0) > 0).sum())
+
+
+def test_offload_counters_closed_forms_and_order_independence(oracle):
+    const = np.tile(np.array([[3, 5]], np.int32), (2, 12, 1))
+    ch, ld = oracle.offload_counters(const, 8)
+    assert list(ch) == [1, 1] and list(ld) == [2, 2]
+    swapped = const.copy()
+    swapped[:, 1::2] = swapped[:, 1::2, ::-1]  # the same SET in another slot order is no change
+    assert [list(v) for v in oracle.offload_counters(swapped, 8)] == [[1, 1], [2, 2]]
+    alt = np.array([[[0, 1], [2, 3]] * 4], np.int32)  # disjoint sets every step
+    ch, ld = oracle.offload_counters(alt, 4)
+    assert ch[0] == 8 and ld[0] == 16
+    # brute force with Python sets on a random trace
+    rng = np.random.default_rng(11)
+    tr = np.argsort(rng.random((3, 40, 6)), axis=-1)[..., :2].astype(np.int32)
+    ch, ld = oracle.offload_counters(tr, 6)
+    for l in range(3):
+        prev, c, n = set(), 0, 0
+        for t in range(40):
+            cur = set(tr[l, t].tolist())
+            if cur != prev:
+                c += 1
+                n += len(cur - prev)
+                prev = cur
+        assert (ch[l], ld[l]) == (c, n)
