@@ -105,6 +105,8 @@ def main():
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="phone_prefill", choices=sorted(WORKLOADS))
+    ap.add_argument("--top-k", type=int, default=None, help="override k (active experts)")
+    ap.add_argument("--experts", type=int, default=None, help="override E (total experts)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run three 256 MiB device copies (a known-size kernel that scales the "
@@ -129,6 +131,10 @@ def main():
     dev = torch.device("cuda:0")
     cfg_name, T = WORKLOADS[args.workload]
     cfg = wl.CONFIGS[cfg_name]
+    if args.top_k is not None or args.experts is not None:
+        # the paper's ablation grid (active experts k, total experts E); no stored Zipf bias then
+        cfg = wl.shrink(cfg, top_k=args.top_k or cfg.top_k, n_experts=args.experts or cfg.n_experts,
+                        zipf=False)
     decode = T == 1
     stack = cfg.n_layers > 1
     steps = args.steps if args.steps is not None else (256 if stack else (2000 if decode else 200))

@@ -596,9 +596,19 @@ static int run_gemm(const moe_shape& s, GemmArgs& g, bool swiglu, hipStream_t st
         fast &= g.seg[i].K % 64 == 0;  // the deep pipeline has no K tail
     }
     if (fast) {
-        // Measured on the phone shape with Zipf-skewed groups: the wide gate/up product (N = 2F)
-        // is fastest with 128 x 256 tiles (64 x 128 per wave); the down projection (N = d) needs
-        // the smaller 128 x 128 tile to have enough workgroups for 256 CUs.
+        // Tile choice, measured on the phone shape (uniform and Zipf-skewed groups): with about
+        // 400 or more rows per expert and a wide output, 256 x 256 x 32 tiles on 8 waves (64 x 128
+        // per wave, two waves per SIMD) are fastest.  With smaller groups a 256-row tile is mostly
+        // padding, and with a narrow output (down projection, rank-r products) there are too few
+        // such tiles for 256 CUs; then 128-row tiles are used (128 x 256 for the gate/up product,
+        // 128 x 128 otherwise).
+        const long long big_tiles = (long long)(g.P / 256 + (g.E + 1) / 2) * ((g.N + (swiglu ? 127 : 255)) / (swiglu ? 128 : 256));
+        if (g.P >= 384 * g.E && big_tiles >= 400) {  // enough 256 x 256 tiles to fill 256 CUs
+            if (swiglu)
+                return dual ? launch_bf16_deep<256, 256, 32, 64, 128, true, true>(g, st)
+                            : launch_bf16_deep<256, 256, 32, 64, 128, true, false>(g, st);
+            return launch_bf16_deep<256, 256, 32, 64, 128, false, false>(g, st);
+        }
         if (swiglu)
             return dual ? launch_bf16_deep<128, 256, 64, 64, 128, true, true>(g, st)
                         : launch_bf16_deep<128, 256, 64, 64, 128, true, false>(g, st);
