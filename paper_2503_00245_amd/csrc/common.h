@@ -37,10 +37,32 @@ struct Store<bf16_t> {
     static __device__ __forceinline__ bf16_t from_f32(float v) { return (bf16_t)v; }  // RNE
 };
 
-// ---- wavefront reductions (butterfly over all 64 lanes; every lane gets the result) ----
+// ---- wavefront reductions: every lane gets the result --------------------------------------
+// Within a row of 16 lanes the exchange is done with DPP modifiers (register-to-register,
+// no LDS round trip): swap neighbours, swap pairs, mirror within 8, mirror within 16.  After
+// those four steps every lane of a row holds the row's result; the four rows are then
+// combined with two cross-lane permutes (xor 16, xor 32).
+constexpr int kDppSwap1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int kDppSwap2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;  // lane i <-> 7 - i within 8
+constexpr int kDppMirror = 0x140;      // lane i <-> 15 - i within 16
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
+}
+template <int CTRL>
+__device__ __forceinline__ int dpp_i32(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, false);
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
+    v += dpp_f32<kDppSwap1>(v);
+    v += dpp_f32<kDppSwap2>(v);
+    v += dpp_f32<kDppHalfMirror>(v);
+    v += dpp_f32<kDppMirror>(v);
+    v += __shfl_xor(v, 16, kWave);
+    v += __shfl_xor(v, 32, kWave);
     return v;
 }
 

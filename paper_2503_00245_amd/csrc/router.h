@@ -18,7 +18,7 @@ __device__ __forceinline__ void router_logits(LoadX load_x, const float* __restr
     float acc[TOK];
 #pragma unroll
     for (int t = 0; t < TOK; ++t) acc[t] = 0.f;
-    for (int i = lane * VEC; i < d; i += kWave * VEC) {
+    auto chunk = [&](int i) {
         f32x4 wv[VEC / 4];
 #pragma unroll
         for (int q = 0; q < VEC; q += 4) wv[q / 4] = *reinterpret_cast<const f32x4*>(we + i + q);
@@ -35,7 +35,14 @@ __device__ __forceinline__ void router_logits(LoadX load_x, const float* __restr
                 acc[t] = fmaf(xv[q + 3], wv[q / 4][3], acc[t]);
             }
         }
-    }
+    };
+    // whole 64-lane chunks have a wave-uniform trip count, so the compiler can unroll the loop
+    // and put several chunks' loads in flight; the ragged tail is one predicated chunk
+    constexpr int CH = kWave * VEC;
+    const int nfull = d / CH;
+#pragma unroll 4
+    for (int c = 0; c < nfull; ++c) chunk(c * CH + lane * VEC);
+    if (nfull * CH + lane * VEC < d) chunk(nfull * CH + lane * VEC);
 #pragma unroll
     for (int t = 0; t < TOK; ++t) out[t] = wave_sum(acc[t]);
 }
@@ -59,15 +66,19 @@ __device__ __forceinline__ RouterPick router_select(int lane, int E, int k, floa
     for (int j = 0; j < k; ++j) {
         float bv = cand;
         int bi = lane;
-#pragma unroll
-        for (int m = 32; m >= 1; m >>= 1) {
-            const float ov = __shfl_xor(bv, m, kWave);
-            const int oi = __shfl_xor(bi, m, kWave);
+        auto take = [&](float ov, int oi) {
             if (ov > bv || (ov == bv && oi < bi)) {
                 bv = ov;
                 bi = oi;
             }
-        }
+        };
+        // (value, index) arg-max all-reduce; every pairing is symmetric, so all lanes agree
+        take(dpp_f32<kDppSwap1>(bv), dpp_i32<kDppSwap1>(bi));
+        take(dpp_f32<kDppSwap2>(bv), dpp_i32<kDppSwap2>(bi));
+        take(dpp_f32<kDppHalfMirror>(bv), dpp_i32<kDppHalfMirror>(bi));
+        take(dpp_f32<kDppMirror>(bv), dpp_i32<kDppMirror>(bi));
+        take(__shfl_xor(bv, 16, kWave), __shfl_xor(bi, 16, kWave));
+        take(__shfl_xor(bv, 32, kWave), __shfl_xor(bi, 32, kWave));
         if (j == 0) vmax = bv;  // the first pick is the row maximum
         if (lane == bi) {
             cand = -INFINITY;
