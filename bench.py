@@ -53,9 +53,15 @@ WORKLOADS = {
     "phone_stack_decode": ("phone_stack", 1),
 }
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs (see profiles/); None until measured for that workload.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of
+# this script (summaries under profiles/), each scaled by what the same counter reads for the 256 MiB
+# device copy of --pmc-calibration (FETCH_SIZE x2.0, WRITE_SIZE x1.0).  None: not measured.
+MEASURED_TRAFFIC_BYTES = {
+    # gemm_bf16_deep_kernel<256,256,32,64,128,SWIGLU>: 246626.5 KiB x 2.0 fetched + 45260.7 KiB written
+    "phone_prefill": int((246626.5 * 2.0 + 45260.7) * 1024),
+    # gemv_kernel<SWIGLU>: 45834.0 KiB x 2.0 fetched + 1452.0 KiB written
+    "phone_decode": int((45834.0 * 2.0 + 1452.0) * 1024),
+}
 
 
 def layer_weight_bytes(cfg):
