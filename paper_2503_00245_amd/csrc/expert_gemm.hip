@@ -20,6 +20,8 @@
 // land on the same XCD and hit in its L2.
 //
 // fp32 problems (correctness-only configuration) use a plain LDS-tiled FMA kernel.
+#include <type_traits>
+
 #include "common.h"
 
 namespace moe {
@@ -437,21 +439,30 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_deep_ker
             }
 #endif
         };
-        for (int kt = 0; kt < nk; kt += 2) {
-            // even step: multiply tile kt (stage 0); r0 is free, r1 holds tile kt+1
-            gload(r0, min((kt + 2) * BK, k_last));
-            compute(0);
-            lstore(1, r1);
-            interleave();
-            __syncthreads();
-            if (kt + 1 >= nk) break;
-            // odd step: multiply tile kt+1 (stage 1); r1 is free, r0 holds tile kt+2
-            gload(r1, min((kt + 3) * BK, k_last));
-            compute(1);
-            lstore(0, r0);
-            interleave();
-            __syncthreads();
-        }
+        // A wave whose WM rows all lie past the end of the group has nothing to multiply: it
+        // keeps filling LDS and meeting the barriers but skips the fragment reads and MFMAs,
+        // which leaves its SIMD and the LDS read port to the waves that do have rows.
+        auto k_loop = [&](auto active) {
+            for (int kt = 0; kt < nk; kt += 2) {
+                // even step: multiply tile kt (stage 0); r0 is free, r1 holds tile kt+1
+                gload(r0, min((kt + 2) * BK, k_last));
+                if (active) compute(0);
+                lstore(1, r1);
+                if (active) interleave();
+                __syncthreads();
+                if (kt + 1 >= nk) break;
+                // odd step: multiply tile kt+1 (stage 1); r1 is free, r0 holds tile kt+2
+                gload(r1, min((kt + 3) * BK, k_last));
+                if (active) compute(1);
+                lstore(0, r0);
+                if (active) interleave();
+                __syncthreads();
+            }
+        };
+        if (row0 + wm * WM < row_end)
+            k_loop(std::true_type{});
+        else
+            k_loop(std::false_type{});
     }
 
     // ---- epilogue (accumulator layout as in gemm_bf16_kernel) -------------------------------------
