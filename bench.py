@@ -15,6 +15,9 @@ synchronisation; one JSON line is printed.
              second pass of K steps through moe_forward_timed (same kernels, same
              inputs; the events are kept out of the tokens/s pass)
   stages     average milliseconds of every stage kernel from that second pass
+  latency_ms median / p10 / p90 of single steps (one event pair per step, own pass)
+  graph_replay_ms_per_step  the same steps captured once into a HIP graph and replayed
+  gpu_state  shader clock and board power from sysfs right before and after the timed steps
   cpu_baseline  the CPU oracle, as it stands, timed on this host on a bounded sample
 
 Workloads (shapes of the benchmark configurations):
@@ -105,6 +108,33 @@ def layer_algorithmic(cfg, T):
     return flops, float(nbytes)
 
 
+def gpu_state():
+    """Clock and power of the first GPU from sysfs (plain file reads; no child process)."""
+    import glob
+    out = {}
+    for dev in sorted(glob.glob("/sys/class/drm/card[0-9]*/device")):
+        try:
+            with open(os.path.join(dev, "pp_dpm_sclk")) as f:
+                cur = [ln.split(":")[1].strip() for ln in f if "*" in ln]
+            out["sclk"] = cur[0].replace("*", "").strip() if cur else None
+        except OSError:
+            continue
+        for name, key, scale in (("power1_average", "power_w", 1e-6), ("power1_input", "power_w", 1e-6),
+                                 ("power1_cap", "power_cap_w", 1e-6)):
+            for path in glob.glob(os.path.join(dev, "hwmon/hwmon*/" + name)):
+                try:
+                    with open(path) as f:
+                        out.setdefault(key, round(int(f.read().strip()) * scale, 1))
+                except (OSError, ValueError):
+                    pass
+        break
+    return out or None
+
+
+def percentile(sorted_vals, q):
+    return sorted_vals[min(len(sorted_vals) - 1, int(q * len(sorted_vals)))]
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -191,6 +221,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    state_before = gpu_state()
     for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
@@ -201,6 +232,45 @@ def main():
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / steps * 1e3
     tokens_per_s = T * steps / elapsed
+
+    state_after = gpu_state()
+
+    # ---- per-step latency spread: one event pair around every step --------------------------
+    n_lat = min(steps, 200)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_lat)]
+    for i, (e0, e1) in enumerate(evs):
+        e0.record()
+        step(warmup + i)
+        e1.record()
+    torch.cuda.synchronize()
+    lat = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+    latency = {"n": n_lat, "median": round(percentile(lat, 0.5), 5), "p10": round(percentile(lat, 0.1), 5),
+               "p90": round(percentile(lat, 0.9), 5)}
+
+    # ---- the same steps replayed from a HIP graph: launch gaps between kernels drop out ------
+    graph_ms = None
+    if not stack:
+        n_in_graph = len(w_structs) if decode else 4
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for i in range(n_in_graph):
+                step(i)
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                for i in range(n_in_graph):
+                    step(i)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        n_rep = max(3, min(steps, 200) // n_in_graph)
+        for _ in range(2):
+            graph.replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(n_rep):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t1) / (n_rep * n_in_graph) * 1e3
 
     # ---- second pass: per-stage durations from HIP events on the launch stream ------------
     stage_sum = {}
@@ -278,7 +348,10 @@ def main():
                    "shared_base": cfg.shared_base, "n_layers": cfg.n_layers, "tokens_per_step": T,
                    "zipf_router_bias": bool(cfg.zipf), "weight_copies_rotated": len(copies)},
         "roofline": roofline, "cpu_baseline": cpu, "stages_ms": {k: round(v, 5) for k, v in stages.items()},
-        "layer": layer, "input_generation_s": round(gen_s, 1),
+        "layer": layer,
+        "latency_ms": latency, "graph_replay_ms_per_step": None if graph_ms is None else round(graph_ms, 5),
+        "gpu_state": {"before": state_before, "after": state_after},
+        "input_generation_s": round(gen_s, 1),
     }
     print(json.dumps(out))
 

@@ -371,7 +371,9 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_deep_ker
             for (int i = 0; i < BI; ++i)
                 *reinterpret_cast<bf16x8*>(bb + lds_off<BK>(ld_row + RPP * i, ld_chunk)) = r.b[i];
         };
-        auto compute = [&](int stage) {
+        // MA = how many of the wave's MT 32-row blocks hold rows of the group (the rest are skipped)
+        auto compute = [&](int stage, auto ma) {
+            constexpr int MA = decltype(ma)::value;
             const char* base = smem + stage * STAGE;
             const char* a0b = base;
             const char* a1b = (DUAL_A && dual) ? base + A_BYTES : base;
@@ -379,9 +381,9 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_deep_ker
 #pragma unroll
             for (int ks = 0; ks < BK / 16; ++ks) {
                 const int chunk = ks * 2 + (lane >> 5);
-                bf16x8 fa[MT], fa1[DUAL_A ? MT : 1], fb[NT];
+                bf16x8 fa[MA], fa1[DUAL_A ? MA : 1], fb[NT];
 #pragma unroll
-                for (int mi = 0; mi < MT; ++mi) {
+                for (int mi = 0; mi < MA; ++mi) {
                     const int r = wm * WM + mi * 32 + (lane & 31);
                     fa[mi] = *reinterpret_cast<const bf16x8*>(a0b + lds_off<BK>(r, chunk));
                     if (DUAL_A) fa1[mi] = *reinterpret_cast<const bf16x8*>(a1b + lds_off<BK>(r, chunk));
@@ -396,7 +398,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_deep_ker
                     fb[ni] = *reinterpret_cast<const bf16x8*>(bb + lds_off<BK>(r, chunk));
                 }
 #pragma unroll
-                for (int mi = 0; mi < MT; ++mi)
+                for (int mi = 0; mi < MA; ++mi)
 #pragma unroll
                     for (int ni = 0; ni < NT; ++ni) {
                         const bf16x8 av = (DUAL_A && SWIGLU && ni >= NT / 2) ? fa1[mi] : fa[mi];
@@ -420,14 +422,15 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_deep_ker
         // Issue order inside a step: the step's global loads and LDS writes are spread through
         // the MFMA sequence (one memory instruction in the shadow of each MFMA) instead of
         // running as separate phases, so a wave's MFMA stream has no load/store-only gaps.
-        auto interleave = [&]() {
+        auto interleave = [&](auto ma) {
 #if defined(__HIP_DEVICE_COMPILE__)
-            constexpr int NM = MT * NT * (BK / 16);           // MFMAs per step
-            constexpr int NR = (MT * NA + NT) * (BK / 16);    // LDS fragment reads per step
+            constexpr int MA = decltype(ma)::value;
+            constexpr int NM = MA * NT * (BK / 16);           // MFMAs per step
+            constexpr int NR = (MA * NA + NT) * (BK / 16);    // LDS fragment reads per step
             constexpr int NL = AI * NA + BI;                  // global loads = LDS writes per step
             constexpr int RPM = (NR + NM - 1) / NM;
             constexpr int LPM = (2 * NL + NM - 1) / NM;
-            __builtin_amdgcn_sched_group_barrier(0x100, MT * NA + NT, 0);  // first fragments
+            __builtin_amdgcn_sched_group_barrier(0x100, MA * NA + NT, 0);  // first fragments
 #pragma unroll
             for (int i = 0; i < NM; ++i) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // one MFMA
@@ -439,30 +442,34 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_deep_ker
             }
 #endif
         };
-        // A wave whose WM rows all lie past the end of the group has nothing to multiply: it
-        // keeps filling LDS and meeting the barriers but skips the fragment reads and MFMAs,
-        // which leaves its SIMD and the LDS read port to the waves that do have rows.
-        auto k_loop = [&](auto active) {
+        // The wave multiplies only those of its 32-row blocks that hold rows of the group.  A wave
+        // with none keeps filling LDS and meeting the barriers but issues no fragment reads or
+        // MFMAs, which leaves its SIMD and the LDS read port to the waves that do have rows.
+        auto k_loop = [&](auto ma) {
+            constexpr int MA = decltype(ma)::value;
             for (int kt = 0; kt < nk; kt += 2) {
                 // even step: multiply tile kt (stage 0); r0 is free, r1 holds tile kt+1
                 gload(r0, min((kt + 2) * BK, k_last));
-                if (active) compute(0);
+                if constexpr (MA > 0) compute(0, ma);
                 lstore(1, r1);
-                if (active) interleave();
+                if constexpr (MA > 0) interleave(ma);
                 __syncthreads();
                 if (kt + 1 >= nk) break;
                 // odd step: multiply tile kt+1 (stage 1); r1 is free, r0 holds tile kt+2
                 gload(r1, min((kt + 3) * BK, k_last));
-                if (active) compute(1);
+                if constexpr (MA > 0) compute(1, ma);
                 lstore(0, r0);
-                if (active) interleave();
+                if constexpr (MA > 0) interleave(ma);
                 __syncthreads();
             }
         };
-        if (row0 + wm * WM < row_end)
-            k_loop(std::true_type{});
-        else
-            k_loop(std::false_type{});
+        const int live = min(MT, max(0, (row_end - row0 - wm * WM + 31) / 32));  // wave-uniform
+        static_assert(MT <= 4, "one k_loop instance per count of live 32-row blocks");
+        if (live == MT) k_loop(std::integral_constant<int, MT>{});
+        else if (live == 0) k_loop(std::integral_constant<int, 0>{});
+        else if (live == 1) k_loop(std::integral_constant<int, 1>{});
+        else if (live == 2) k_loop(std::integral_constant<int, (MT > 2 ? 2 : 1)>{});
+        else k_loop(std::integral_constant<int, (MT > 3 ? 3 : 1)>{});
     }
 
     // ---- epilogue (accumulator layout as in gemm_bf16_kernel) -------------------------------------
