@@ -78,6 +78,7 @@ def _route_gpu(dev, x_t, w_t, E, k, act, want_probs=True):
     (65, 256, 64, 8, "bf16", True),     # one expert per lane
     (33, 264, 5, 1, "f32", False),      # k = 1, d not a multiple of the wave stride
     (40, 512, 6, 6, "bf16", False),     # k = E
+    (19, 128, 64, 64, "bf16", True),    # the largest E and k the library takes
 ])
 def test_route_matches_oracle(dev, oracle, T, d, E, k, dtype, bias):
     cfg = _cfg(d=d, E=E, k=k, dtype=dtype, seed=300 + T)
@@ -148,6 +149,28 @@ def test_permute_matches_oracle_bit_exact(dev, oracle, T, k, E):
     assert np.array_equal(bits_of(xp), x_np[r_perm // k])
     # unpermute(permute(x)) is the identity on the payload
     assert np.array_equal(bits_of(xp)[r_inv].reshape(T, k, d)[:, 0], x_np)
+
+
+@pytest.mark.parametrize("T,k,E", [(1_000_000, 4, 64), ((1 << 21) - 1, 8, 8)])
+def test_permute_large_without_payload(dev, oracle, T, k, E):
+    # several hundred workgroups per kernel of the multi-pass sort; the second case is the
+    # largest pair count the library accepts (T k just under 2^24)
+    rng = np.random.default_rng(E * 1000 + k)
+    keys = np.argsort(rng.random((T, E), dtype=np.float32) + np.linspace(0.6, 0, E, dtype=np.float32),
+                      axis=1)[:, :k].astype(np.int32)
+    shape = pkg.make_shape(T, 8, 8, E, k, 0, pkg.MOE_BF16)
+    P = T * k
+    assert P < (1 << 24)
+    off = torch.full((E + 1,), -1, dtype=torch.int32, device=dev)
+    perm = torch.full((P,), -1, dtype=torch.int32, device=dev)
+    inv = torch.full((P,), -1, dtype=torch.int32, device=dev)
+    ws = pkg.alloc_workspace(shape, dev)
+    pkg.moe_permute(shape, to_device(keys, dev), off, perm, inv, None, None, ws)
+    torch.cuda.synchronize()
+    r_off, r_perm, r_inv = oracle.permute(keys, E)
+    assert np.array_equal(off.cpu().numpy(), r_off)
+    assert np.array_equal(perm.cpu().numpy(), r_perm)
+    assert np.array_equal(inv.cpu().numpy(), r_inv)
 
 
 # ------------------------------------------------------------------------------- moe_expert_ffn
