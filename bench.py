@@ -143,6 +143,7 @@ def main():
     ap.add_argument("--workload", default="phone_prefill", choices=sorted(WORKLOADS))
     ap.add_argument("--top-k", type=int, default=None, help="override k (active experts)")
     ap.add_argument("--experts", type=int, default=None, help="override E (total experts)")
+    ap.add_argument("--tokens", type=int, default=None, help="override the workload's tokens per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run three 256 MiB device copies (a known-size kernel that scales the "
@@ -166,6 +167,8 @@ def main():
         sys.exit(1)
     dev = torch.device("cuda:0")
     cfg_name, T = WORKLOADS[args.workload]
+    if args.tokens is not None:
+        T = args.tokens
     cfg = wl.CONFIGS[cfg_name]
     if args.top_k is not None or args.experts is not None:
         # the paper's ablation grid (active experts k, total experts E); no stored Zipf bias then

@@ -21,10 +21,20 @@
 //
 // fp32 problems (correctness-only configuration) use a plain LDS-tiled FMA kernel.
 #include <type_traits>
+#include <utility>
 
 #include "common.h"
 
 namespace moe {
+
+template <int... I, typename F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, F&& f) {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+    static_for_impl(std::make_integer_sequence<int, N>{}, static_cast<F&&>(f));
+}
 
 struct GemmSeg {
     const void* A0;     // [*, K]
@@ -288,10 +298,16 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(c
 // its last row and only feed outputs the epilogue never stores), so the loop has no
 // divergent control flow.  (Direct global->LDS loads were measured here and rejected:
 // on this chip they stall co-issued MFMAs far more than register loads do.)
-template <int BM, int BN, int BK, int WM, int WN, bool SWIGLU, bool DUAL_A>
-__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_deep_kernel(const GemmArgs g) {
+//
+// KG > 1: the workgroup holds KG groups of (BM / WM) * (BN / WN) waves.  Every group runs
+// the whole pipeline on its own 1/KG of the k-steps, with its own LDS stages, and the
+// groups' accumulators meet in LDS at the end, added in group order.  This is for products
+// with fewer tiles than CUs and a long K, where the serial chain of k-steps of a single
+// tile, not the chip's throughput, sets the time.  Needs K % (KG * BK) == 0.
+template <int BM, int BN, int BK, int WM, int WN, bool SWIGLU, bool DUAL_A, int NS, int KG>
+__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KG) void gemm_bf16_deep_kernel(const GemmArgs g) {
     constexpr int WAVES_N = BN / WN;
-    constexpr int NTHR = (BM / WM) * WAVES_N * 64;
+    constexpr int NTHR = (BM / WM) * WAVES_N * 64;  // threads of one k-group
     constexpr int MT = WM / 32, NT = WN / 32;
     static_assert(!SWIGLU || NT % 2 == 0, "gate and up fragments pair up");
     constexpr int CPR = BK / 8;
@@ -308,10 +324,12 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_deep_ker
     constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;
     const int n0 = nt * BN_OUT;
 
-    const int tid = threadIdx.x;
+    const int kg = threadIdx.x / NTHR;   // k-group of this wave
+    const int tid = threadIdx.x % NTHR;  // thread within the group
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
     const int ld_row = tid / CPR, ld_chunk = tid % CPR;
+    char* const gmem = smem + kg * (2 * STAGE);  // this group's two stages
 
     f32x16 acc[MT][NT];
 #pragma unroll
@@ -331,6 +349,9 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_deep_ker
         const bool dual = DUAL_A && sg.A1 != sg.A0;
         const bf16_t* B0 = static_cast<const bf16_t*>(sg.B0) + (size_t)e * sg.strideB;
         const bf16_t* B1 = SWIGLU ? static_cast<const bf16_t*>(sg.B1) + (size_t)e * sg.strideB : B0;
+        const int nk = K / (BK * KG);        // k-steps of this group (the same for every group)
+        const int k_begin = kg * nk * BK;
+        const int k_last = (nk - 1) * BK;    // relative to k_begin
 
         const bf16_t* pa[AI];
         const bf16_t* pa1[DUAL_A ? AI : 1];
@@ -338,7 +359,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_deep_ker
 #pragma unroll
         for (int i = 0; i < AI; ++i) {
             const int s = min(row0 + ld_row + RPP * i, row_end - 1);
-            const size_t off = (size_t)src_row(g, sg, s) * K + ld_chunk * 8;
+            const size_t off = (size_t)src_row(g, sg, s) * K + k_begin + ld_chunk * 8;
             pa[i] = static_cast<const bf16_t*>(sg.A0) + off;
             if (DUAL_A) pa1[i] = static_cast<const bf16_t*>(sg.A1) + off;
         }
@@ -346,7 +367,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_deep_ker
         for (int i = 0; i < BI; ++i) {
             const int j = ld_row + RPP * i;
             const int n = min(SWIGLU ? n0 + (j % (BN / 2)) : n0 + j, g.N - 1);
-            pb[i] = ((SWIGLU && i >= BI / 2) ? B1 : B0) + (size_t)n * K + ld_chunk * 8;
+            pb[i] = ((SWIGLU && i >= BI / 2) ? B1 : B0) + (size_t)n * K + k_begin + ld_chunk * 8;
         }
 
         auto gload = [&](Regs& r, int k0) {
@@ -359,7 +380,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_deep_ker
             for (int i = 0; i < BI; ++i) r.b[i] = *reinterpret_cast<const bf16x8*>(pb[i] + k0);
         };
         auto lstore = [&](int stage, const Regs& r) {
-            char* base = smem + stage * STAGE;
+            char* base = gmem + stage * STAGE;
 #pragma unroll
             for (int i = 0; i < AI; ++i) {
                 *reinterpret_cast<bf16x8*>(base + lds_off<BK>(ld_row + RPP * i, ld_chunk)) = r.a[i];
@@ -374,7 +395,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_deep_ker
         // MA = how many of the wave's MT 32-row blocks hold rows of the group (the rest are skipped)
         auto compute = [&](int stage, auto ma) {
             constexpr int MA = decltype(ma)::value;
-            const char* base = smem + stage * STAGE;
+            const char* base = gmem + stage * STAGE;
             const char* a0b = base;
             const char* a1b = (DUAL_A && dual) ? base + A_BYTES : base;
             const char* bb = base + A_BYTES * NA;
@@ -407,17 +428,18 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_deep_ker
             }
         };
 
-        const int nk = K / BK;
-        const int k_last = K - BK;
-        Regs r0, r1;
-        // Every load and LDS write below is unconditional (k offsets are clamped to the last
-        // tile, whose re-fetch near the end is harmless): the outstanding-load count at each
-        // wait is then a compile-time constant and a wait for tile kt+1 never also waits for
-        // the younger loads of tile kt+2.
+        // NS register sets: tile kt is multiplied out of LDS while tile kt+1 waits in registers to
+        // be written to the other LDS stage at the end of the step and tiles kt+2 .. kt+NS are in
+        // flight from memory.  Every load and LDS write below is unconditional (k offsets are
+        // clamped to the last tile, whose re-fetch near the end is harmless): the
+        // outstanding-load count at each wait is then a compile-time constant and a wait for
+        // tile kt+1 never also waits for the younger loads behind it.
+        constexpr int UNR = (NS % 2 == 0) ? NS : 2 * NS;  // steps until (set, stage) repeat
+        Regs r[NS];
         __syncthreads();  // the previous segment's readers are done with both stages
-        gload(r0, 0);
-        gload(r1, min(BK, k_last));
-        lstore(0, r0);
+#pragma unroll
+        for (int q = 0; q < NS; ++q) gload(r[q], min(q * BK, k_last));
+        lstore(0, r[0]);
         __syncthreads();
         // Issue order inside a step: the step's global loads and LDS writes are spread through
         // the MFMA sequence (one memory instruction in the shadow of each MFMA) instead of
@@ -447,20 +469,27 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_deep_ker
         // MFMAs, which leaves its SIMD and the LDS read port to the waves that do have rows.
         auto k_loop = [&](auto ma) {
             constexpr int MA = decltype(ma)::value;
-            for (int kt = 0; kt < nk; kt += 2) {
-                // even step: multiply tile kt (stage 0); r0 is free, r1 holds tile kt+1
-                gload(r0, min((kt + 2) * BK, k_last));
-                if constexpr (MA > 0) compute(0, ma);
-                lstore(1, r1);
+            // step S of the unrolled body: multiply tile kt (stage S & 1), refill set S % NS (its
+            // tile went to LDS at the end of the previous step) with tile kt + NS, write tile
+            // kt + 1 (set (S + 1) % NS) to the other stage
+            auto step = [&](auto sc, int kt) {
+                constexpr int S = decltype(sc)::value;
+                gload(r[S % NS], min((kt + NS) * BK, k_last));
+                if constexpr (MA > 0) compute(S & 1, ma);
+                lstore((S & 1) ^ 1, r[(S + 1) % NS]);
                 if constexpr (MA > 0) interleave(ma);
                 __syncthreads();
-                if (kt + 1 >= nk) break;
-                // odd step: multiply tile kt+1 (stage 1); r1 is free, r0 holds tile kt+2
-                gload(r1, min((kt + 3) * BK, k_last));
-                if constexpr (MA > 0) compute(1, ma);
-                lstore(0, r0);
-                if constexpr (MA > 0) interleave(ma);
-                __syncthreads();
+            };
+            for (int kt = 0; kt < nk; kt += UNR) {
+                bool more = true;
+                static_for<UNR>([&](auto sc) {
+                    constexpr int S = decltype(sc)::value;
+                    if (more) {
+                        step(sc, kt + S);
+                        more = kt + S + 1 < nk;
+                    }
+                });
+                if (!more) break;
             }
         };
         const int live = min(MT, max(0, (row_end - row0 - wm * WM + 31) / 32));  // wave-uniform
@@ -470,6 +499,32 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_deep_ker
         else if (live == 1) k_loop(std::integral_constant<int, 1>{});
         else if (live == 2) k_loop(std::integral_constant<int, (MT > 2 ? 2 : 1)>{});
         else k_loop(std::integral_constant<int, (MT > 3 ? 3 : 1)>{});
+    }
+
+    // ---- k-groups 1 .. KG-1 hand their sums to group 0 through LDS (every stage is idle now) ------
+    if constexpr (KG > 1) {
+        constexpr int NACC = MT * NT * 16;
+        static_assert(NACC * NTHR * 4 <= 2 * STAGE, "a group's accumulators fit in its own stages");
+        float* mine = reinterpret_cast<float*>(gmem) + tid;
+        if (kg > 0) {
+#pragma unroll
+            for (int mi = 0; mi < MT; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NT; ++ni)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) mine[((mi * NT + ni) * 16 + i) * NTHR] = acc[mi][ni][i];
+        }
+        __syncthreads();
+        if (kg > 0) return;
+        for (int q = 1; q < KG; ++q) {
+            const float* src = reinterpret_cast<const float*>(smem + q * (2 * STAGE)) + tid;
+#pragma unroll
+            for (int mi = 0; mi < MT; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NT; ++ni)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) acc[mi][ni][i] += src[((mi * NT + ni) * 16 + i) * NTHR];
+        }
     }
 
     // ---- epilogue (accumulator layout as in gemm_bf16_kernel) -------------------------------------
@@ -573,17 +628,20 @@ static int launch_bf16(GemmArgs& g, hipStream_t st) {
     return launch_status();
 }
 
-template <int BM, int BN, int BK, int WM, int WN, bool SWIGLU, bool DUAL_A>
+template <int BM, int BN, int BK, int WM, int WN, bool SWIGLU, bool DUAL_A, int NS = 2, int KG = 1>
 static int launch_bf16_deep(GemmArgs& g, hipStream_t st) {
     constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;
-    constexpr int NTHR = (BM / WM) * (BN / WN) * 64;
+    constexpr int NTHR = (BM / WM) * (BN / WN) * 64 * KG;
+    static_assert(NTHR <= 1024, "workgroup size");
     g.m_tiles_max = g.P / BM + g.E;
     g.n_tiles = (g.N + BN_OUT - 1) / BN_OUT;
     const int total = g.m_tiles_max * g.n_tiles;
     const int grid = (total + 7) / 8 * 8;
-    constexpr size_t lds = 2 * ((size_t)BM * BK * 2 * (DUAL_A ? 2 : 1) + (size_t)BN * BK * 2);
+    constexpr size_t lds = KG * 2 * ((size_t)BM * BK * 2 * (DUAL_A ? 2 : 1) + (size_t)BN * BK * 2);
     static_assert(lds <= 160 * 1024, "LDS stages exceed the CU's 160 KB");
-    auto kern = gemm_bf16_deep_kernel<BM, BN, BK, WM, WN, SWIGLU, DUAL_A>;
+    for (int i = 0; i < g.nseg; ++i)
+        if (g.seg[i].K % (BK * KG) != 0) return MOE_ERR_UNSUPPORTED;  // callers check before choosing KG
+    auto kern = gemm_bf16_deep_kernel<BM, BN, BK, WM, WN, SWIGLU, DUAL_A, NS, KG>;
     static bool attr_set = false;
     if (lds > 32 * 1024 && !attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -614,12 +672,13 @@ static int run_gemm(const moe_shape& s, GemmArgs& g, bool swiglu, hipStream_t st
         fast &= g.seg[i].K % 64 == 0;  // the deep pipeline has no K tail
     }
     if (fast) {
-        // Tile choice, measured on the phone shape (uniform and Zipf-skewed groups): with about
-        // 400 or more rows per expert and a wide output, 256 x 256 x 32 tiles on 8 waves (64 x 128
-        // per wave, two waves per SIMD) are fastest.  With smaller groups a 256-row tile is mostly
-        // padding, and with a narrow output (down projection, rank-r products) there are too few
-        // such tiles for 256 CUs; then 128-row tiles are used (128 x 256 for the gate/up product,
-        // 128 x 128 otherwise).
+        // Tile choice, measured on the phone and wearables shapes with uniform and Zipf-skewed
+        // groups.  With about 400 or more rows per expert and a wide output, 256 x 256 x 32 tiles on
+        // 8 waves (64 x 128 per wave, two waves per SIMD) are fastest.  Below that the products
+        // are bound by streaming the weights, and what counts is enough workgroups to pull them
+        // with every CU: 128 x 128 x 64 tiles (two workgroups per CU), 64-row tiles once the
+        // groups hold about 128 rows or fewer, and for a plain product with few tiles and a
+        // long K two k-groups per workgroup.
         const long long big_tiles = (long long)(g.P / 256 + (g.E + 1) / 2) * ((g.N + (swiglu ? 127 : 255)) / (swiglu ? 128 : 256));
         if (g.P >= 384 * g.E && big_tiles >= 400) {  // enough 256 x 256 tiles to fill 256 CUs
             if (swiglu)
@@ -627,9 +686,18 @@ static int run_gemm(const moe_shape& s, GemmArgs& g, bool swiglu, hipStream_t st
                             : launch_bf16_deep<256, 256, 32, 64, 128, true, false>(g, st);
             return launch_bf16_deep<256, 256, 32, 64, 128, false, false>(g, st);
         }
-        if (swiglu)
-            return dual ? launch_bf16_deep<128, 256, 64, 64, 128, true, true>(g, st)
-                        : launch_bf16_deep<128, 256, 64, 64, 128, true, false>(g, st);
+        const bool small_groups = g.P <= 128 * g.E;
+        if (swiglu) {
+            if (small_groups)
+                return dual ? launch_bf16_deep<64, 128, 64, 32, 64, true, true>(g, st)
+                            : launch_bf16_deep<64, 128, 64, 32, 64, true, false>(g, st);
+            return dual ? launch_bf16_deep<128, 128, 64, 64, 64, true, true>(g, st)
+                        : launch_bf16_deep<128, 128, 64, 64, 64, true, false>(g, st);
+        }
+        const long long tiles128 = (long long)(g.P / 128 + (g.E + 1) / 2) * ((g.N + 127) / 128);
+        bool k_pairs = true;
+        for (int i = 0; i < g.nseg; ++i) k_pairs &= g.seg[i].K % 128 == 0;
+        if (tiles128 < 160 && k_pairs) return launch_bf16_deep<64, 128, 64, 32, 64, false, false, 2, 2>(g, st);
         return launch_bf16_deep<128, 128, 64, 64, 64, false, false>(g, st);
     }
     if (swiglu)
