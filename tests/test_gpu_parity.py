@@ -48,7 +48,8 @@ def _check_routing(oracle, x_np, w_np, k, idx_gpu, gate_gpu, probs_gpu=None):
         kth = np.sort(logits[t])[::-1][k - 1]
         assert len(set(idx_gpu[t])) == k
         assert np.all(logits[t, idx_gpu[t]] >= kth - 1e-4), "inadmissible choice on ambiguous token"
-    assert amb.sum() <= max(2, x_np.shape[0] // 200), "too many ambiguous tokens for this recipe"
+    # k + 1 adjacent ranks can each be a near-tie, so the allowance grows with k
+    assert amb.sum() <= max(2, x_np.shape[0] * k // 400), "too many ambiguous tokens for this recipe"
     assert np.allclose(gate_gpu[same], gate[same], rtol=2e-5, atol=1e-7)
     assert np.allclose(gate_gpu.sum(1), 1.0, atol=1e-6)
     if probs_gpu is not None:
@@ -283,9 +284,17 @@ def test_forward_tiny_fp32_config(dev, oracle):
     _forward_case(dev, oracle, cfg, 5, residual=True)
 
 
-@pytest.mark.parametrize("T", [1, 2, 3, 130, 512])
+@pytest.mark.parametrize("T", [1, 2, 3, 130, 512, 1024, 20000])
 def test_forward_wearables_config(dev, oracle, T):
+    # 130 and 512: 64-row GEMM tiles (and two k-groups for the down product); 1024: 128-row tiles;
+    # 20000: 256-row tiles over many m-tiles and the multi-workgroup sort inside the forward
     _forward_case(dev, oracle, wl.CONFIGS["wearables"], T, sample=96)
+
+
+@pytest.mark.parametrize("T", [1, 40, 700])
+def test_forward_many_experts(dev, oracle, T):
+    cfg = _cfg(name="e64", d=256, F=512, E=64, k=8, dtype="bf16", seed=640, std=0.05)
+    _forward_case(dev, oracle, cfg, T)
 
 
 @pytest.fixture(scope="module")
