@@ -80,6 +80,8 @@ def _route_gpu(dev, x_t, w_t, E, k, act, want_probs=True):
     (33, 264, 5, 1, "f32", False),      # k = 1, d not a multiple of the wave stride
     (40, 512, 6, 6, "bf16", False),     # k = E
     (19, 128, 64, 64, "bf16", True),    # the largest E and k the library takes
+    (1500, 1024, 8, 2, "bf16", True),   # many tokens: eight per workgroup, ragged last tile
+    (1028, 256, 64, 8, "f32", False),
 ])
 def test_route_matches_oracle(dev, oracle, T, d, E, k, dtype, bias):
     cfg = _cfg(d=d, E=E, k=k, dtype=dtype, seed=300 + T)
