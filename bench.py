@@ -336,6 +336,11 @@ def main():
         if not (decode or stack):
             n_sample = max(probe_n, n_sample // probe_n * probe_n)
         took = run_oracle(n_sample)
+        passes = 1
+        while took < 0.8 * args.cpu_seconds and passes < 4 and not (decode or stack):
+            took += run_oracle(n_sample)  # the whole batch is short work for the host: go over it again
+            passes += 1
+        n_sample *= passes
         cpu = {"value": round(n_sample / took, 3), "unit": "tokens/s",
                "cores": moe_oracle.num_threads(), "kind": "oracle",
                "sample": f"{n_sample} token(s) of the {args.workload} workload through the fp64 C "
