@@ -678,7 +678,7 @@ static int run_gemm(const moe_shape& s, GemmArgs& g, bool swiglu, hipStream_t st
         // are bound by streaming the weights, and what counts is enough workgroups to pull them
         // with every CU: 128 x 128 x 64 tiles (two workgroups per CU), 64-row tiles once the
         // groups hold about 128 rows or fewer, and for a plain product with few tiles and a
-        // long K two k-groups per workgroup.
+        // long K two k-groups per workgroup (on 64 x 64 tiles when the groups average 32 rows or less).
         const long long big_tiles = (long long)(g.P / 256 + (g.E + 1) / 2) * ((g.N + (swiglu ? 127 : 255)) / (swiglu ? 128 : 256));
         if (g.P >= 384 * g.E && big_tiles >= 400) {  // enough 256 x 256 tiles to fill 256 CUs
             if (swiglu)
@@ -697,7 +697,10 @@ static int run_gemm(const moe_shape& s, GemmArgs& g, bool swiglu, hipStream_t st
         const long long tiles128 = (long long)(g.P / 128 + (g.E + 1) / 2) * ((g.N + 127) / 128);
         bool k_pairs = true;
         for (int i = 0; i < g.nseg; ++i) k_pairs &= g.seg[i].K % 128 == 0;
-        if (tiles128 < 160 && k_pairs) return launch_bf16_deep<64, 128, 64, 32, 64, false, false, 2, 2>(g, st);
+        if (tiles128 < 160 && k_pairs) {
+            if (g.P <= 32 * g.E) return launch_bf16_deep<64, 64, 64, 32, 32, false, false, 2, 2>(g, st);
+            return launch_bf16_deep<64, 128, 64, 32, 64, false, false, 2, 2>(g, st);
+        }
         return launch_bf16_deep<128, 128, 64, 64, 64, false, false>(g, st);
     }
     if (swiglu)
