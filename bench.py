@@ -18,6 +18,8 @@ synchronisation; one JSON line is printed.
   latency_ms median / p10 / p90 of single steps (one event pair per step, own pass)
   graph_replay_ms_per_step  the same steps captured once into a HIP graph and replayed
   gpu_state  shader clock and board power from sysfs right before and after the timed steps
+  decode     (default workload only) the same layer at one token per step: ms per step, tokens/s
+             and the HBM roofline of its dominant kernel -- the metric's third part
   cpu_baseline  the CPU oracle, as it stands, timed on this host on a bounded sample
 
 Workloads (shapes of the benchmark configurations):
@@ -145,6 +147,8 @@ def main():
     ap.add_argument("--experts", type=int, default=None, help="override E (total experts)")
     ap.add_argument("--tokens", type=int, default=None, help="override the workload's tokens per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode-leg", action="store_true",
+                    help="default workload only: skip the single-token decode measurement appended as 'decode'")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run three 256 MiB device copies (a known-size kernel that scales the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -166,201 +170,220 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     dev = torch.device("cuda:0")
-    cfg_name, T = WORKLOADS[args.workload]
-    if args.tokens is not None:
-        T = args.tokens
-    cfg = wl.CONFIGS[cfg_name]
-    if args.top_k is not None or args.experts is not None:
-        # the paper's ablation grid (active experts k, total experts E); no stored Zipf bias then
-        cfg = wl.shrink(cfg, top_k=args.top_k or cfg.top_k, n_experts=args.experts or cfg.n_experts,
-                        zipf=False)
-    decode = T == 1
-    stack = cfg.n_layers > 1
-    steps = args.steps if args.steps is not None else (256 if stack else (2000 if decode else 200))
-    warmup = args.warmup if args.warmup is not None else (8 if stack else (50 if decode else 10))
+    weight_cache = {}
 
-    def dev_t(a):
-        if a is None:
-            return None
-        if a.dtype == np.uint16:
-            return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).to(dev)
-        return torch.from_numpy(a).to(dev)
+    def run_workload(workload, tokens, steps_arg, warmup_arg, want_cpu):
+        cfg_name, T = WORKLOADS[workload]
+        if tokens is not None:
+            T = tokens
+        cfg = wl.CONFIGS[cfg_name]
+        if args.top_k is not None or args.experts is not None:
+            # the paper's ablation grid (active experts k, total experts E); no stored Zipf bias then
+            cfg = wl.shrink(cfg, top_k=args.top_k or cfg.top_k, n_experts=args.experts or cfg.n_experts,
+                            zipf=False)
+        decode = T == 1
+        stack = cfg.n_layers > 1
+        steps = steps_arg if steps_arg is not None else (256 if stack else (2000 if decode else 200))
+        warmup = warmup_arg if warmup_arg is not None else (8 if stack else (50 if decode else 10))
 
-    # ---- inputs: generated on the host from the seed, then resident in HBM ---------------
-    t_gen = time.time()
-    if stack:
-        layers_np = wl.make_stack_weights(cfg, workers=8)
-    else:
-        layers_np = [wl.make_layer_weights(cfg)]
-    layers_t = [{k: dev_t(v) for k, v in w.items()} for w in layers_np]
-    n_inputs = 256 if decode else 4
-    xs_np = [wl.make_inputs(cfg, T, step=i) for i in range(n_inputs)]
-    xs = [dev_t(x) for x in xs_np]
-    # cold-cache rotation for single-layer decode: enough copies to exceed the LLC several times
-    copies = [layers_t]
-    if decode and not stack:
-        n_copies = max(2, int(np.ceil(1.5e9 / layer_weight_bytes(cfg))))
-        for _ in range(n_copies - 1):
-            copies.append([{k: (None if v is None else v.clone()) for k, v in layers_t[0].items()}])
-    gen_s = time.time() - t_gen
+        def dev_t(a):
+            if a is None:
+                return None
+            if a.dtype == np.uint16:
+                return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).to(dev)
+            return torch.from_numpy(a).to(dev)
 
-    shape = pkg.shape_for(layers_t[0], T, cfg.top_k, pkg.MOE_BF16)
-    ws = pkg.alloc_workspace(shape, dev)
-    y = torch.empty_like(xs[0])
-    w_structs = [[pkg.make_weights(w) for w in c] for c in copies]
-
-    def step(i):
-        ws_i = w_structs[i % len(w_structs)]
+        # ---- inputs: generated on the host from the seed, then resident in HBM ---------------
+        t_gen = time.time()
         if stack:
-            pkg.moe_stack_forward(shape, ws_i, xs[i % n_inputs], y, None, ws)
+            layers_np = wl.make_stack_weights(cfg, workers=8)
         else:
-            pkg.moe_forward(shape, ws_i[0], xs[i % n_inputs], y, None, None, ws)
+            if cfg.name not in weight_cache:
+                weight_cache.clear()  # one layer's host copy at a time
+                weight_cache[cfg.name] = wl.make_layer_weights(cfg)
+            layers_np = [weight_cache[cfg.name]]
+        layers_t = [{k: dev_t(v) for k, v in w.items()} for w in layers_np]
+        n_inputs = 256 if decode else 4
+        xs_np = [wl.make_inputs(cfg, T, step=i) for i in range(n_inputs)]
+        xs = [dev_t(x) for x in xs_np]
+        # cold-cache rotation for single-layer decode: enough copies to exceed the LLC several times
+        copies = [layers_t]
+        if decode and not stack:
+            n_copies = max(2, int(np.ceil(1.5e9 / layer_weight_bytes(cfg))))
+            for _ in range(n_copies - 1):
+                copies.append([{k: (None if v is None else v.clone()) for k, v in layers_t[0].items()}])
+        gen_s = time.time() - t_gen
 
-    if args.pmc_calibration:
-        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
+        shape = pkg.shape_for(layers_t[0], T, cfg.top_k, pkg.MOE_BF16)
+        ws = pkg.alloc_workspace(shape, dev)
+        y = torch.empty_like(xs[0])
+        w_structs = [[pkg.make_weights(w) for w in c] for c in copies]
+
+        def step(i):
+            ws_i = w_structs[i % len(w_structs)]
+            if stack:
+                pkg.moe_stack_forward(shape, ws_i, xs[i % n_inputs], y, None, ws)
+            else:
+                pkg.moe_forward(shape, ws_i[0], xs[i % n_inputs], y, None, None, ws)
+
+        if args.pmc_calibration:
+            src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+            dst = torch.empty_like(src)
+            for _ in range(3):
+                dst.copy_(src)
+            torch.cuda.synchronize()
+            del src, dst
+
+        state_before = gpu_state()
+        for i in range(warmup):
+            step(i)
         torch.cuda.synchronize()
-        del src, dst
+        t0 = time.perf_counter()
+        for i in range(steps):
+            step(warmup + i)
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        ms_per_step = elapsed / steps * 1e3
+        tokens_per_s = T * steps / elapsed
 
-    state_before = gpu_state()
-    for i in range(warmup):
-        step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(steps):
-        step(warmup + i)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed / steps * 1e3
-    tokens_per_s = T * steps / elapsed
+        state_after = gpu_state()
 
-    state_after = gpu_state()
+        # ---- per-step latency spread: one event pair around every step --------------------------
+        n_lat = min(steps, 200)
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_lat)]
+        for i, (e0, e1) in enumerate(evs):
+            e0.record()
+            step(warmup + i)
+            e1.record()
+        torch.cuda.synchronize()
+        lat = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+        latency = {"n": n_lat, "median": round(percentile(lat, 0.5), 5), "p10": round(percentile(lat, 0.1), 5),
+                   "p90": round(percentile(lat, 0.9), 5)}
 
-    # ---- per-step latency spread: one event pair around every step --------------------------
-    n_lat = min(steps, 200)
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_lat)]
-    for i, (e0, e1) in enumerate(evs):
-        e0.record()
-        step(warmup + i)
-        e1.record()
-    torch.cuda.synchronize()
-    lat = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
-    latency = {"n": n_lat, "median": round(percentile(lat, 0.5), 5), "p10": round(percentile(lat, 0.1), 5),
-               "p90": round(percentile(lat, 0.9), 5)}
-
-    # ---- the same steps replayed from a HIP graph: launch gaps between kernels drop out ------
-    graph_ms = None
-    if not stack:
-        n_in_graph = len(w_structs) if decode else 4
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            for i in range(n_in_graph):
-                step(i)
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph, stream=side):
+        # ---- the same steps replayed from a HIP graph: launch gaps between kernels drop out ------
+        graph_ms = None
+        if not stack:
+            n_in_graph = len(w_structs) if decode else 4
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
                 for i in range(n_in_graph):
                     step(i)
-        torch.cuda.current_stream().wait_stream(side)
-        torch.cuda.synchronize()
-        n_rep = max(3, min(steps, 200) // n_in_graph)
-        for _ in range(2):
-            graph.replay()
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        for _ in range(n_rep):
-            graph.replay()
-        torch.cuda.synchronize()
-        graph_ms = (time.perf_counter() - t1) / (n_rep * n_in_graph) * 1e3
-
-    # ---- second pass: per-stage durations from HIP events on the launch stream ------------
-    stage_sum = {}
-    order = []
-    n_timed = min(steps, 200) if not stack else min(steps, 8)
-    single = pkg.shape_for(layers_t[0], T, cfg.top_k, pkg.MOE_BF16, residual=stack)
-    for i in range(n_timed):
-        ws_i = w_structs[i % len(w_structs)]
-        for l, wst in enumerate(ws_i):
-            for name, ms in pkg.moe_forward_timed(single, wst, xs[(i + l) % n_inputs], y, ws):
-                if name not in stage_sum:
-                    stage_sum[name] = 0.0
-                    order.append(name)
-                stage_sum[name] += ms
-    n_launch = n_timed * len(w_structs[0])
-    stages = {n: stage_sum[n] / n_launch for n in order}
-
-    kname, bound, work, unit = dominant_kernel_work(cfg, T)
-    kms = stages[kname]
-    if bound == "hbm":
-        achieved = work / (kms * 1e-3) / 1e9
-        peak = HBM_PEAK_GBS
-    else:
-        achieved = work / (kms * 1e-3) / 1e12
-        peak = MFMA_BF16_PEAK_TFLOPS
-    roofline = {"bound": bound, "achieved": round(achieved, 2), "peak": peak, "unit": unit,
-                "frac": round(achieved / peak, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
-                "kernel": kname, "kernel_ms": round(kms, 5), "algorithmic_per_launch": work}
-    flops, wbytes = layer_algorithmic(cfg, T)
-    n_l = cfg.n_layers
-    layer = {"mfma_frac_of_peak": round(flops * n_l / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
-             "hbm_frac_of_peak": round(wbytes * n_l / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-             "algorithmic_flops": flops * n_l, "algorithmic_weight_bytes": wbytes * n_l,
-             "sum_of_stage_ms": round(sum(stages.values()), 5)}
-
-    # ---- CPU oracle baseline on a bounded sample of the same workload -------------------------
-    cpu = None
-    if not args.no_cpu_baseline:
-        from oracle import moe_oracle
-        k = cfg.top_k
-
-        def run_oracle(n_tok):
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph, stream=side):
+                    for i in range(n_in_graph):
+                        step(i)
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            n_rep = max(3, min(steps, 200) // n_in_graph)
+            for _ in range(2):
+                graph.replay()
+            torch.cuda.synchronize()
             t1 = time.perf_counter()
+            for _ in range(n_rep):
+                graph.replay()
+            torch.cuda.synchronize()
+            graph_ms = (time.perf_counter() - t1) / (n_rep * n_in_graph) * 1e3
+
+        # ---- second pass: per-stage durations from HIP events on the launch stream ------------
+        stage_sum = {}
+        order = []
+        n_timed = min(steps, 200) if not stack else min(steps, 8)
+        single = pkg.shape_for(layers_t[0], T, cfg.top_k, pkg.MOE_BF16, residual=stack)
+        for i in range(n_timed):
+            ws_i = w_structs[i % len(w_structs)]
+            for l, wst in enumerate(ws_i):
+                for name, ms in pkg.moe_forward_timed(single, wst, xs[(i + l) % n_inputs], y, ws):
+                    if name not in stage_sum:
+                        stage_sum[name] = 0.0
+                        order.append(name)
+                    stage_sum[name] += ms
+        n_launch = n_timed * len(w_structs[0])
+        stages = {n: stage_sum[n] / n_launch for n in order}
+
+        kname, bound, work, unit = dominant_kernel_work(cfg, T)
+        kms = stages[kname]
+        if bound == "hbm":
+            achieved = work / (kms * 1e-3) / 1e9
+            peak = HBM_PEAK_GBS
+        else:
+            achieved = work / (kms * 1e-3) / 1e12
+            peak = MFMA_BF16_PEAK_TFLOPS
+        roofline = {"bound": bound, "achieved": round(achieved, 2), "peak": peak, "unit": unit,
+                    "frac": round(achieved / peak, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(workload) if tokens is None else None,
+                    "kernel": kname, "kernel_ms": round(kms, 5), "algorithmic_per_launch": work}
+        flops, wbytes = layer_algorithmic(cfg, T)
+        n_l = cfg.n_layers
+        layer = {"mfma_frac_of_peak": round(flops * n_l / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                 "hbm_frac_of_peak": round(wbytes * n_l / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                 "algorithmic_flops": flops * n_l, "algorithmic_weight_bytes": wbytes * n_l,
+                 "sum_of_stage_ms": round(sum(stages.values()), 5)}
+
+        # ---- CPU oracle baseline on a bounded sample of the same workload -------------------------
+        cpu = None
+        if want_cpu:
+            from oracle import moe_oracle
+            k = cfg.top_k
+
+            def run_oracle(n_tok):
+                t1 = time.perf_counter()
+                if stack:
+                    for i in range(n_tok):
+                        moe_oracle.stack_forward(layers_np, xs_np[i % n_inputs], k)
+                elif decode:
+                    for i in range(n_tok):
+                        moe_oracle.forward(layers_np[0], xs_np[i % n_inputs], k)
+                else:
+                    moe_oracle.forward(layers_np[0], np.ascontiguousarray(xs_np[0][:n_tok]), k)
+                return time.perf_counter() - t1
+
+            probe_n = 1 if (decode or stack) else min(T, 2 * moe_oracle.num_threads())
+            probe = run_oracle(probe_n)
+            n_sample = int(max(probe_n, min(T if not decode else 4096,
+                                            probe_n * args.cpu_seconds / max(probe, 1e-6))))
             if stack:
-                for i in range(n_tok):
-                    moe_oracle.stack_forward(layers_np, xs_np[i % n_inputs], k)
-            elif decode:
-                for i in range(n_tok):
-                    moe_oracle.forward(layers_np[0], xs_np[i % n_inputs], k)
-            else:
-                moe_oracle.forward(layers_np[0], np.ascontiguousarray(xs_np[0][:n_tok]), k)
-            return time.perf_counter() - t1
+                n_sample = max(1, min(n_sample, 4))
+            if not (decode or stack):
+                n_sample = max(probe_n, n_sample // probe_n * probe_n)
+            took = run_oracle(n_sample)
+            passes = 1
+            while took < 0.8 * args.cpu_seconds and passes < 4 and not (decode or stack):
+                took += run_oracle(n_sample)  # the whole batch is short work for the host: go over it again
+                passes += 1
+            n_sample *= passes
+            cpu = {"value": round(n_sample / took, 3), "unit": "tokens/s",
+                   "cores": moe_oracle.num_threads(), "kind": "oracle",
+                   "sample": f"{n_sample} token(s) of the {workload} workload through the fp64 C "
+                             f"oracle in {took:.2f} s"}
 
-        probe_n = 1 if (decode or stack) else min(T, 2 * moe_oracle.num_threads())
-        probe = run_oracle(probe_n)
-        n_sample = int(max(probe_n, min(T if not decode else 4096,
-                                        probe_n * args.cpu_seconds / max(probe, 1e-6))))
-        if stack:
-            n_sample = max(1, min(n_sample, 4))
-        if not (decode or stack):
-            n_sample = max(probe_n, n_sample // probe_n * probe_n)
-        took = run_oracle(n_sample)
-        passes = 1
-        while took < 0.8 * args.cpu_seconds and passes < 4 and not (decode or stack):
-            took += run_oracle(n_sample)  # the whole batch is short work for the host: go over it again
-            passes += 1
-        n_sample *= passes
-        cpu = {"value": round(n_sample / took, 3), "unit": "tokens/s",
-               "cores": moe_oracle.num_threads(), "kind": "oracle",
-               "sample": f"{n_sample} token(s) of the {args.workload} workload through the fp64 C "
-                         f"oracle in {took:.2f} s"}
+        out = {
+            "metric": "moe_layer_tokens_per_s", "value": round(tokens_per_s, 2), "unit": "tokens/s",
+            "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 5),
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+            "data": "synthetic",
+            "config": {"workload": workload, "d_model": cfg.d_model, "d_ff": cfg.d_ff,
+                       "n_experts": cfg.n_experts, "top_k": cfg.top_k, "rank": cfg.rank,
+                       "shared_base": cfg.shared_base, "n_layers": cfg.n_layers, "tokens_per_step": T,
+                       "zipf_router_bias": bool(cfg.zipf), "weight_copies_rotated": len(copies)},
+            "roofline": roofline, "cpu_baseline": cpu, "stages_ms": {k: round(v, 5) for k, v in stages.items()},
+            "layer": layer,
+            "latency_ms": latency, "graph_replay_ms_per_step": None if graph_ms is None else round(graph_ms, 5),
+            "gpu_state": {"before": state_before, "after": state_after},
+            "input_generation_s": round(gen_s, 1),
+        }
+        return out
 
-    out = {
-        "metric": "moe_layer_tokens_per_s", "value": round(tokens_per_s, 2), "unit": "tokens/s",
-        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 5),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
-        "data": "synthetic",
-        "config": {"workload": args.workload, "d_model": cfg.d_model, "d_ff": cfg.d_ff,
-                   "n_experts": cfg.n_experts, "top_k": cfg.top_k, "rank": cfg.rank,
-                   "shared_base": cfg.shared_base, "n_layers": cfg.n_layers, "tokens_per_step": T,
-                   "zipf_router_bias": bool(cfg.zipf), "weight_copies_rotated": len(copies)},
-        "roofline": roofline, "cpu_baseline": cpu, "stages_ms": {k: round(v, 5) for k, v in stages.items()},
-        "layer": layer,
-        "latency_ms": latency, "graph_replay_ms_per_step": None if graph_ms is None else round(graph_ms, 5),
-        "gpu_state": {"before": state_before, "after": state_after},
-        "input_generation_s": round(gen_s, 1),
-    }
+    out = run_workload(args.workload, args.tokens, args.steps, args.warmup, not args.no_cpu_baseline)
+    plain = args.tokens is None and args.top_k is None and args.experts is None
+    if args.workload == "phone_prefill" and plain and not args.no_decode_leg:
+        # the metric has three parts: tokens/s and MFMA use at prefill (above), HBM use at
+        # single-token decode (here, same layer, same process)
+        d = run_workload("phone_decode", None, None, None, False)
+        out["decode"] = {k: d[k] for k in ("ms_per_step", "value", "unit", "steps", "warmup", "roofline",
+                                           "stages_ms", "latency_ms", "graph_replay_ms_per_step")}
+        out["decode"]["workload"] = "phone_decode"
+        out["decode"]["layer_hbm_frac_of_peak"] = d["layer"]["hbm_frac_of_peak"]
+        out["decode"]["weight_copies_rotated"] = d["config"]["weight_copies_rotated"]
     print(json.dumps(out))
 
 
