@@ -10,14 +10,16 @@
 // and linear-layer weights [out, in], and exactly what an MFMA lane wants: 8 consecutive
 // k of one row per 16-byte read.
 //
-// bf16 kernel: 256 threads = 4 waves, block tile BM x BN x 64, wave tile WM x WN built
-// from v_mfma_f32_32x32x16_bf16, fp32 accumulators in registers.  Global -> registers ->
-// LDS with a two-stage LDS ring (loads of tile kt+1 are in flight while tile kt is
-// multiplied).  LDS rows are 128 bytes (64 bf16) with the 16-byte chunk index XOR-ed by
-// (row >> 1) & 7, which spreads both the row-wise fills and the column-of-rows MFMA
-// operand reads over all banks.  Tiles are enumerated n-tile major / m-tile minor and the
-// workgroup id is remapped so that consecutive tiles (which share the same weight tile)
-// land on the same XCD and hit in its L2.
+// bf16 kernels: block tile BM x BN x BK on (BM / WM) * (BN / WN) waves, wave tile WM x WN built
+// from v_mfma_f32_32x32x16_bf16, fp32 accumulators in registers.  Global -> registers -> LDS
+// with two LDS stages; the fast path (gemm_bf16_deep_kernel, K a multiple of BK) keeps a
+// second register set so that three tiles are in flight, the fallback (gemm_bf16_kernel)
+// zero-fills ragged K.  LDS rows are BK bf16 wide with the 16-byte chunk index XOR-ed by a
+// function of the row, which spreads both the row-wise fills and the column-of-rows MFMA
+// operand reads over all banks.  Tiles are enumerated expert-major, then n-tile, then the
+// expert's m-tiles, and the workgroup id is remapped so that each XCD walks a contiguous
+// eighth of that order (consecutive tiles share a weight tile and hit in that XCD's L2).
+// run_gemm picks the tile shape from the pair count and the output width.
 //
 // fp32 problems (correctness-only configuration) use a plain LDS-tiled FMA kernel.
 #include <type_traits>
