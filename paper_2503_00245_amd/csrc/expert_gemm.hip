@@ -52,6 +52,7 @@ struct GemmArgs {
     GemmSeg seg[2];
     int nseg;
     void* C;            // [P, N]
+    void* C1;           // PLAIN only, deep kernel: second product (A1 . B1) of the same shape, or NULL
     int N;
     const int32_t* offsets;  // [E+1]
     const int32_t* row_map;  // [P] or NULL
@@ -59,7 +60,7 @@ struct GemmArgs {
     int E;
     int P;
     int m_tiles_max;
-    int n_tiles;
+    int n_tiles;        // n-tiles of the launch (twice those of one product when C1 is set)
 };
 
 // Workgroup -> output tile.  Tiles are ordered expert-major, then n-tile, then the expert's
@@ -324,6 +325,9 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KG) void gemm_bf16_dee
     int e, row0, row_end, nt;
     if (!find_tile(g.offsets, g.E, BM, g.n_tiles, e, row0, row_end, nt)) return;
     constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;
+    // two plain products in one launch: the upper half of the n-tiles belongs to (A1, B1, C1)
+    const bool second = !SWIGLU && g.C1 != nullptr && nt >= g.n_tiles / 2;
+    if (second) nt -= g.n_tiles / 2;
     const int n0 = nt * BN_OUT;
 
     const int kg = threadIdx.x / NTHR;   // k-group of this wave
@@ -349,7 +353,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KG) void gemm_bf16_dee
         const GemmSeg& sg = g.seg[sidx];
         const int K = sg.K;
         const bool dual = DUAL_A && sg.A1 != sg.A0;
-        const bf16_t* B0 = static_cast<const bf16_t*>(sg.B0) + (size_t)e * sg.strideB;
+        const bf16_t* B0 = static_cast<const bf16_t*>(second ? sg.B1 : sg.B0) + (size_t)e * sg.strideB;
         const bf16_t* B1 = SWIGLU ? static_cast<const bf16_t*>(sg.B1) + (size_t)e * sg.strideB : B0;
         const int nk = K / (BK * KG);        // k-steps of this group (the same for every group)
         const int k_begin = kg * nk * BK;
@@ -362,7 +366,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KG) void gemm_bf16_dee
         for (int i = 0; i < AI; ++i) {
             const int s = min(row0 + ld_row + RPP * i, row_end - 1);
             const size_t off = (size_t)src_row(g, sg, s) * K + k_begin + ld_chunk * 8;
-            pa[i] = static_cast<const bf16_t*>(sg.A0) + off;
+            pa[i] = static_cast<const bf16_t*>(second ? sg.A1 : sg.A0) + off;
             if (DUAL_A) pa1[i] = static_cast<const bf16_t*>(sg.A1) + off;
         }
 #pragma unroll
@@ -530,7 +534,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KG) void gemm_bf16_dee
     }
 
     // ---- epilogue (accumulator layout as in gemm_bf16_kernel) -------------------------------------
-    bf16_t* C = static_cast<bf16_t*>(g.C);
+    bf16_t* C = static_cast<bf16_t*>(second ? g.C1 : g.C);
 #pragma unroll
     for (int mi = 0; mi < MT; ++mi) {
 #pragma unroll
@@ -636,7 +640,7 @@ static int launch_bf16_deep(GemmArgs& g, hipStream_t st) {
     constexpr int NTHR = (BM / WM) * (BN / WN) * 64 * KG;
     static_assert(NTHR <= 1024, "workgroup size");
     g.m_tiles_max = g.P / BM + g.E;
-    g.n_tiles = (g.N + BN_OUT - 1) / BN_OUT;
+    g.n_tiles = (g.N + BN_OUT - 1) / BN_OUT * ((!SWIGLU && g.C1) ? 2 : 1);
     const int total = g.m_tiles_max * g.n_tiles;
     const int grid = (total + 7) / 8 * 8;
     constexpr size_t lds = KG * 2 * ((size_t)BM * BK * 2 * (DUAL_A ? 2 : 1) + (size_t)BN * BK * 2);
@@ -666,13 +670,26 @@ static int launch_simple(GemmArgs& g, hipStream_t st) {
 
 static int run_gemm(const moe_shape& s, GemmArgs& g, bool swiglu, hipStream_t st) {
     if (g.P == 0) return MOE_OK;
-    if (s.act_dtype == MOE_F32)
-        return swiglu ? launch_simple<float, true>(g, st) : launch_simple<float, false>(g, st);
-    bool dual = false, fast = true;
+    const int n_eff = g.N * (g.C1 ? 2 : 1);  // output columns of the launch
+    bool dual = false, fast = s.act_dtype != MOE_F32;
     for (int i = 0; i < g.nseg; ++i) {
         dual |= swiglu && g.seg[i].A1 != g.seg[i].A0;
         fast &= g.seg[i].K % 64 == 0;  // the deep pipeline has no K tail
     }
+    if (g.C1 && !fast) {  // only the deep kernel takes two products per launch: run them one by one
+        GemmArgs second = g;
+        second.C = g.C1;
+        second.C1 = nullptr;
+        for (int i = 0; i < g.nseg; ++i) {
+            second.seg[i].A0 = g.seg[i].A1;
+            second.seg[i].B0 = g.seg[i].B1;
+        }
+        g.C1 = nullptr;
+        const int rc = run_gemm(s, g, swiglu, st);
+        return rc != MOE_OK ? rc : run_gemm(s, second, swiglu, st);
+    }
+    if (s.act_dtype == MOE_F32)
+        return swiglu ? launch_simple<float, true>(g, st) : launch_simple<float, false>(g, st);
     if (fast) {
         // Tile choice, measured on the phone and wearables shapes with uniform and Zipf-skewed
         // groups.  With about 400 or more rows per expert and a wide output, 256 x 256 x 32 tiles on
@@ -681,7 +698,7 @@ static int run_gemm(const moe_shape& s, GemmArgs& g, bool swiglu, hipStream_t st
         // with every CU: 128 x 128 x 64 tiles (two workgroups per CU), 64-row tiles once the
         // groups hold about 128 rows or fewer, and for a plain product with few tiles and a
         // long K two k-groups per workgroup (on 64 x 64 tiles when the groups average 32 rows or less).
-        const long long big_tiles = (long long)(g.P / 256 + (g.E + 1) / 2) * ((g.N + (swiglu ? 127 : 255)) / (swiglu ? 128 : 256));
+        const long long big_tiles = (long long)(g.P / 256 + (g.E + 1) / 2) * ((n_eff + (swiglu ? 127 : 255)) / (swiglu ? 128 : 256));
         if (g.P >= 384 * g.E && big_tiles >= 400) {  // enough 256 x 256 tiles to fill 256 CUs
             if (swiglu)
                 return dual ? launch_bf16_deep<256, 256, 32, 64, 128, true, true>(g, st)
@@ -696,7 +713,7 @@ static int run_gemm(const moe_shape& s, GemmArgs& g, bool swiglu, hipStream_t st
             return dual ? launch_bf16_deep<128, 128, 64, 64, 64, true, true>(g, st)
                         : launch_bf16_deep<128, 128, 64, 64, 64, true, false>(g, st);
         }
-        const long long tiles128 = (long long)(g.P / 128 + (g.E + 1) / 2) * ((g.N + 127) / 128);
+        const long long tiles128 = (long long)(g.P / 128 + (g.E + 1) / 2) * ((n_eff + 127) / 128);
         bool k_pairs = true;
         for (int i = 0; i < g.nseg; ++i) k_pairs &= g.seg[i].K % 128 == 0;
         if (tiles128 < 160 && k_pairs) {
@@ -741,17 +758,12 @@ int launch_expert_ffn(const moe_shape& s, const moe_weights& w, const void* x,
         g.E = E; g.P = P;
         return g;
     };
-    if (r > 0) {  // tg = x R_g^T, tu = x R_u^T   [P, r]
+    if (r > 0) {  // tg = x R_g^T, tu = x R_u^T   [P, r], both in one launch
         GemmArgs g = fresh();
-        g.nseg = 1; g.N = r; g.C = tg;
-        g.seg[0] = GemmSeg{x, x, w.rg, w.rg, (long long)r * d, d, gather};
+        g.nseg = 1; g.N = r; g.C = tg; g.C1 = tu;
+        g.seg[0] = GemmSeg{x, x, w.rg, w.ru, (long long)r * d, d, gather};
         if ((rc = run_gemm(s, g, false, st)) != MOE_OK) return rc;
-        stage_mark(timer, "gemm_rank_gate");
-        g = fresh();
-        g.nseg = 1; g.N = r; g.C = tu;
-        g.seg[0] = GemmSeg{x, x, w.ru, w.ru, (long long)r * d, d, gather};
-        if ((rc = run_gemm(s, g, false, st)) != MOE_OK) return rc;
-        stage_mark(timer, "gemm_rank_up");
+        stage_mark(timer, "gemm_rank_gate_up");
     }
     {  // h = silu(M_gate x) * (M_up x)   [P, F]
         GemmArgs g = fresh();
