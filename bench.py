@@ -165,7 +165,9 @@ def main():
     import paper_2503_00245_amd as pkg
     import workloads as wl
 
-    pkg.lib()  # fail loudly if the HIP library is missing
+    from paper_2503_00245_amd import build as hip_build
+    hip_build.ensure_built()  # compiles only when no library is there
+    pkg.lib()  # fails loudly if the HIP library is still missing
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)

@@ -51,5 +51,11 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+def ensure_built() -> str:
+    """Build only when no library is there (tests, the smoke run and the benchmark call this;
+    the binding itself never builds: a missing library is an error there)."""
+    return LIB if os.path.exists(LIB) else build()
+
+
 if __name__ == "__main__":
     print(build(verbose=True))

@@ -12,6 +12,13 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 
 
+@pytest.fixture(scope="session", autouse=True)
+def _hip_library():
+    """The tests load the library that is built; only when there is none do they compile it."""
+    from paper_2503_00245_amd import build as hip_build
+    return hip_build.ensure_built()
+
+
 @pytest.fixture(scope="session")
 def oracle():
     from oracle import build as obuild
