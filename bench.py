@@ -89,10 +89,13 @@ def dominant_kernel_work(cfg, T):
         else:
             nbytes = k * 2 * F * r * 2 + (2 * F * d * 2 if cfg.shared_base else 0)
         return "gemv_gate_up_swiglu", "hbm", float(nbytes), "GB/s"
-    flops = 4.0 * P * F * (r if r else d)
+    if cfg.shared_base and k > 1:
+        # the shared base meets every token once (not once per pair): its gate and up products
+        # are one plain launch over T rows, the longest kernel of this workload
+        return "gemm_base_gate_up", "mfma", 4.0 * T * F * d, "TFLOP/s"
     if cfg.shared_base:
-        flops += 4.0 * P * F * d
-    return "gemm_gate_up_swiglu", "mfma", flops, "TFLOP/s"
+        return "gemm_gate_up_swiglu", "mfma", 4.0 * P * F * (r + d), "TFLOP/s"
+    return "gemm_gate_up_swiglu", "mfma", 4.0 * P * F * (r if r else d), "TFLOP/s"
 
 
 def layer_algorithmic(cfg, T):
@@ -104,7 +107,8 @@ def layer_algorithmic(cfg, T):
         per_expert = 3 * d * F * 2
         nbytes = min(P, E) * per_expert if T == 1 else E * per_expert
     else:
-        flops = 6.0 * P * r * (d + F) + (6.0 * P * d * F if cfg.shared_base else 0)
+        # a shared base is applied once per token: gate/up on x_t, down on the gate-mixed hidden vector
+        flops = 6.0 * P * r * (d + F) + (6.0 * T * d * F if cfg.shared_base else 0)
         per_expert = 3 * r * (d + F) * 2
         nbytes = (min(P, E) if T == 1 else E) * per_expert + (3 * d * F * 2 if cfg.shared_base else 0)
     return flops, float(nbytes)
@@ -304,6 +308,8 @@ def main():
         stages = {n: stage_sum[n] / n_launch for n in order}
 
         kname, bound, work, unit = dominant_kernel_work(cfg, T)
+        if kname not in stages:  # a shape the per-token base path does not take: base work per pair
+            kname, work = "gemm_gate_up_swiglu", 4.0 * T * cfg.top_k * cfg.d_ff * (cfg.rank + cfg.d_model)
         kms = stages[kname]
         if bound == "hbm":
             achieved = work / (kms * 1e-3) / 1e9

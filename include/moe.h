@@ -177,7 +177,7 @@ MOE_API int moe_stack_forward(const moe_shape* shape, const moe_weights* layers,
  *   stage_names [MOE_MAX_STAGES] host, out or NULL: static strings naming each stage
  *   n_stages    host, out: how many stages ran
  */
-#define MOE_MAX_STAGES 8
+#define MOE_MAX_STAGES 12
 MOE_API int moe_forward_timed(const moe_shape* shape, const moe_weights* weights, const void* x,
                               void* y, void* workspace, size_t workspace_bytes, void* stream,
                               float* stage_ms, const char** stage_names, int32_t* n_stages);

@@ -189,7 +189,7 @@ def moe_stack_forward(shape: MoeShape, layers: Sequence[MoeWeights], x, y, topk_
         0 if workspace is None else workspace.numel(), _stream(y.device)))
 
 
-MAX_STAGES = 8
+MAX_STAGES = 12
 
 
 def moe_forward_timed(shape: MoeShape, weights: MoeWeights, x, y, workspace):

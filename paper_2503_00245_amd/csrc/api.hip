@@ -38,7 +38,7 @@ static int validate_weights(const moe_shape& s, const moe_weights* w, bool need_
 
 // Workspace carving; every region starts 256-byte aligned.
 struct Workspace {
-    size_t topk_idx, topk_gate, offsets, perm, inv_perm, sort_scratch, y_perm, ffn_scratch,
+    size_t topk_idx, topk_gate, offsets, perm, inv_perm, sort_scratch, y_perm, y_base, ffn_scratch,
         decode_scratch, stack_tmp, total;
 };
 
@@ -58,6 +58,7 @@ static Workspace carve(const moe_shape& s) {
     ws.inv_perm = take(P * sizeof(int32_t));
     ws.sort_scratch = take(permute_scratch_bytes((int)P, s.n_experts));
     ws.y_perm = take(P * s.d_model * elt_size(s.act_dtype));
+    ws.y_base = take(token_base_supported(s) ? (size_t)s.n_tokens * s.d_model * elt_size(s.act_dtype) : 0);
     ws.ffn_scratch = take(ffn_scratch_bytes(s));
     ws.decode_scratch = take(decode_scratch_bytes(s));
     ws.stack_tmp = take((size_t)s.n_tokens * s.d_model * elt_size(s.act_dtype));
@@ -84,11 +85,19 @@ static int forward_impl(const moe_shape& s, const moe_weights& w, const void* x,
     if (rc != MOE_OK) return rc;
     stage_mark(timer, "permute");
     // the gather of token rows into expert order is fused into the first GEMM's A loads
+    const void* residual = (s.flags & MOE_FLAG_RESIDUAL) ? x : nullptr;
+    if (token_base_supported(s)) {  // shared base: its products run once per token
+        rc = launch_expert_ffn_token_base(s, w, x, perm, inv_perm, gate, offsets, wsp + ws.y_perm,
+                                          wsp + ws.y_base, wsp + ws.ffn_scratch, st, timer);
+        if (rc != MOE_OK) return rc;
+        rc = launch_combine(s, wsp + ws.y_perm, inv_perm, gate, residual, y, st, wsp + ws.y_base);
+        stage_mark(timer, "combine");
+        return rc;
+    }
     rc = launch_expert_ffn(s, w, x, perm, s.top_k, offsets, wsp + ws.y_perm, wsp + ws.ffn_scratch, st,
                            timer);
     if (rc != MOE_OK) return rc;
-    rc = launch_combine(s, wsp + ws.y_perm, inv_perm, gate,
-                        (s.flags & MOE_FLAG_RESIDUAL) ? x : nullptr, y, st);
+    rc = launch_combine(s, wsp + ws.y_perm, inv_perm, gate, residual, y, st);
     stage_mark(timer, "combine");
     return rc;
 }

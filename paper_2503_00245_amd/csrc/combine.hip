@@ -1,5 +1,5 @@
 // Gate-weighted combine back to token order:
-//   y[t,:] = sum_{j<k} gate[t,j] * y_perm[inv_perm[t*k+j], :]  (+ residual[t,:])
+//   y[t,:] = sum_{j<k} gate[t,j] * y_perm[inv_perm[t*k+j], :]  (+ residual[t,:]) (+ addend[t,:])
 // (Sec. 1 / Sec. 2.1: the gate sets each selected expert's contribution.)  One workgroup
 // per token, 16-byte loads, fp32 accumulation in ascending j, one rounding at the store.
 #include "common.h"
@@ -11,6 +11,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ y_pe
                                                       const int32_t* __restrict__ inv_perm,
                                                       const float* __restrict__ gate,
                                                       const T* __restrict__ residual,
+                                                      const T* __restrict__ addend,
                                                       T* __restrict__ y, int d, int k, int P) {
     typedef Store<T> S;
     constexpr int VEC = S::VEC;
@@ -32,6 +33,11 @@ __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ y_pe
 #pragma unroll
             for (int q = 0; q < VEC; ++q) acc[q] += S::get(r, q);
         }
+        if (addend) {
+            const vec_t r = *reinterpret_cast<const vec_t*>(addend + (size_t)t * d + i);
+#pragma unroll
+            for (int q = 0; q < VEC; ++q) acc[q] += S::get(r, q);
+        }
         vec_t o;
 #pragma unroll
         for (int q = 0; q < VEC; ++q) o[q] = S::from_f32(acc[q]);
@@ -40,17 +46,19 @@ __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ y_pe
 }
 
 int launch_combine(const moe_shape& s, const void* y_perm, const int32_t* inv_perm,
-                   const float* topk_gate, const void* residual, void* y, hipStream_t st) {
+                   const float* topk_gate, const void* residual, void* y, hipStream_t st,
+                   const void* addend) {
     if (s.n_tokens == 0) return MOE_OK;
     const int P = s.n_tokens * s.top_k;
     dim3 grid(s.n_tokens), block(256);
     if (s.act_dtype == MOE_F32)
         hipLaunchKernelGGL(combine_kernel<float>, grid, block, 0, st, (const float*)y_perm, inv_perm,
-                           topk_gate, (const float*)residual, (float*)y, s.d_model, s.top_k, P);
+                           topk_gate, (const float*)residual, (const float*)addend, (float*)y, s.d_model,
+                           s.top_k, P);
     else
         hipLaunchKernelGGL(combine_kernel<bf16_t>, grid, block, 0, st, (const bf16_t*)y_perm,
-                           inv_perm, topk_gate, (const bf16_t*)residual, (bf16_t*)y, s.d_model,
-                           s.top_k, P);
+                           inv_perm, topk_gate, (const bf16_t*)residual, (const bf16_t*)addend, (bf16_t*)y,
+                           s.d_model, s.top_k, P);
     return launch_status();
 }
 

@@ -107,8 +107,10 @@ int launch_permute(int P, int E, const int32_t* topk_idx, int32_t* offsets, int3
 int launch_gather_rows(const moe_shape& s, const int32_t* perm, const void* x, void* x_perm,
                        hipStream_t st);
 
+// addend: optional second per-token term [T, d] in the activation type (beside the residual)
 int launch_combine(const moe_shape& s, const void* y_perm, const int32_t* inv_perm,
-                   const float* topk_gate, const void* residual, void* y, hipStream_t st);
+                   const float* topk_gate, const void* residual, void* y, hipStream_t st,
+                   const void* addend = nullptr);
 
 // Grouped expert FFN on P sorted rows.  a_row_map/a_row_div: optional gather of the input
 // rows (row of sorted slot s is x[a_row_map[s] / a_row_div]); NULL = x is already grouped.
@@ -116,6 +118,16 @@ size_t ffn_scratch_bytes(const moe_shape& s);
 int launch_expert_ffn(const moe_shape& s, const moe_weights& w, const void* x,
                       const int32_t* a_row_map, int a_row_div, const int32_t* offsets,
                       void* y_perm, void* scratch, hipStream_t st, StageTimer* timer = nullptr);
+
+// Shared-base experts M_e = M0 + L_e R_e (Sec. 2.2, Eq. 1 with a base shared by all experts), prefill,
+// with the token of every sorted slot known: the base products run once per token instead
+// of once per (token, expert) pair.  y_perm [P, d] receives only the low-rank part of the down
+// projection and y_base [T, d] the shared part, to be added in the combine.
+bool token_base_supported(const moe_shape& s);
+int launch_expert_ffn_token_base(const moe_shape& s, const moe_weights& w, const void* x,
+                                 const int32_t* perm, const int32_t* inv_perm, const float* topk_gate,
+                                 const int32_t* offsets, void* y_perm, void* y_base, void* scratch,
+                                 hipStream_t st, StageTimer* timer = nullptr);
 
 // Single-token layer: experts chosen on the device from topk_idx, weights streamed once.
 size_t decode_scratch_bytes(const moe_shape& s);

@@ -61,7 +61,19 @@ struct GemmArgs {
     int P;
     int m_tiles_max;
     int n_tiles;        // n-tiles of the launch (twice those of one product when C1 is set)
+    // SWIGLU, deep kernel: per-token rows added to the two accumulators before the activation
+    // (the token of sorted slot s is row_map[s] / row_div), [*, N] in the activation type, or NULL
+    const void* add0;
+    const void* add1;
 };
+
+// Group e's row range; offsets == NULL means one group holding all P rows (a plain product).
+__device__ __forceinline__ int group_begin(const int32_t* __restrict__ offsets, int e) {
+    return offsets ? offsets[e] : 0;
+}
+__device__ __forceinline__ int group_end(const int32_t* __restrict__ offsets, int e, int P) {
+    return offsets ? offsets[e + 1] : P;
+}
 
 // Workgroup -> output tile.  Tiles are ordered expert-major, then n-tile, then the expert's
 // own m-tiles, so neighbouring tiles share the expert's activation rows (and, for equal
@@ -69,20 +81,21 @@ struct GemmArgs {
 // takes the x-th contiguous eighth of that order, which keeps each XCD's L2 working set to
 // about one expert's rows plus the weight tiles it is streaming.  The grid is an upper
 // bound (group sizes live on the device); surplus workgroups return false.
-__device__ __forceinline__ bool find_tile(const int32_t* __restrict__ offsets, int E, int BM,
+__device__ __forceinline__ bool find_tile(const int32_t* __restrict__ offsets, int E, int P, int BM,
                                           int n_tiles, int& e_out, int& row0, int& row_end,
                                           int& nt_out) {
     int total = 0;
-    for (int e = 0; e < E; ++e) total += (offsets[e + 1] - offsets[e] + BM - 1) / BM;
+    for (int e = 0; e < E; ++e)
+        total += (group_end(offsets, e, P) - group_begin(offsets, e) + BM - 1) / BM;
     total *= n_tiles;
     const int per_xcd = (total + 7) / 8;
     const int slot = blockIdx.x >> 3;
     const int L = (blockIdx.x & 7) * per_xcd + slot;
     if (slot >= per_xcd || L >= total) return false;
     int before = 0;
-    int prev = offsets[0];
+    int prev = group_begin(offsets, 0);
     for (int e = 0; e < E; ++e) {
-        const int next = offsets[e + 1];
+        const int next = group_end(offsets, e, P);
         const int mtiles = (next - prev + BM - 1) / BM;
         const int here = mtiles * n_tiles;
         if (L < before + here) {
@@ -100,12 +113,12 @@ __device__ __forceinline__ bool find_tile(const int32_t* __restrict__ offsets, i
 }
 
 // m-tile index (over all experts, in expert order) -> expert and row range
-__device__ __forceinline__ bool find_m_tile(const int32_t* __restrict__ offsets, int E, int BM,
+__device__ __forceinline__ bool find_m_tile(const int32_t* __restrict__ offsets, int E, int P, int BM,
                                             int mt, int& e_out, int& row0, int& row_end) {
     int acc = 0;
-    int prev = offsets[0];
+    int prev = group_begin(offsets, 0);
     for (int e = 0; e < E; ++e) {
-        const int next = offsets[e + 1];
+        const int next = group_end(offsets, e, P);
         const int tiles = (next - prev + BM - 1) / BM;
         if (mt < acc + tiles) {
             e_out = e;
@@ -151,7 +164,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(c
 
     // ---- which tile --------------------------------------------------------------------------
     int e, row0, row_end, nt;
-    if (!find_tile(g.offsets, g.E, BM, g.n_tiles, e, row0, row_end, nt)) return;
+    if (!find_tile(g.offsets, g.E, g.P, BM, g.n_tiles, e, row0, row_end, nt)) return;
     constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;  // output columns per block
     const int n0 = nt * BN_OUT;
 
@@ -323,7 +336,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KG) void gemm_bf16_dee
     extern __shared__ __align__(16) char smem[];
 
     int e, row0, row_end, nt;
-    if (!find_tile(g.offsets, g.E, BM, g.n_tiles, e, row0, row_end, nt)) return;
+    if (!find_tile(g.offsets, g.E, g.P, BM, g.n_tiles, e, row0, row_end, nt)) return;
     constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;
     // two plain products in one launch: the upper half of the n-tiles belongs to (A1, B1, C1)
     const bool second = !SWIGLU && g.C1 != nullptr && nt >= g.n_tiles / 2;
@@ -533,6 +546,34 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KG) void gemm_bf16_dee
         }
     }
 
+    // ---- per-token addends: all their loads are issued before the first output store, so that
+    //      none of them has to wait behind a store it might alias -----------------------------------
+    if constexpr (SWIGLU) {
+        if (g.add0) {
+            const bf16_t* add0 = static_cast<const bf16_t*>(g.add0);
+            const bf16_t* add1 = static_cast<const bf16_t*>(g.add1);
+#pragma unroll
+            for (int mi = 0; mi < MT; ++mi) {
+                int tok[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int row = min(row0 + wm * WM + mi * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3), row_end - 1);
+                    tok[i] = min(max(g.row_map[row], 0), g.P - 1) / g.row_div;
+                }
+#pragma unroll
+                for (int ni = 0; ni < NT / 2; ++ni) {
+                    const int col = min(n0 + wn * (WN / 2) + ni * 32 + (lane & 31), g.N - 1);
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const size_t at = (size_t)tok[i] * g.N + col;
+                        acc[mi][ni][i] += (float)add0[at];
+                        acc[mi][ni + NT / 2][i] += (float)add1[at];
+                    }
+                }
+            }
+        }
+    }
+
     // ---- epilogue (accumulator layout as in gemm_bf16_kernel) -------------------------------------
     bf16_t* C = static_cast<bf16_t*>(second ? g.C1 : g.C);
 #pragma unroll
@@ -562,7 +603,7 @@ __global__ __launch_bounds__(256) void gemm_simple_kernel(const GemmArgs g) {
     const int mt = blockIdx.x % g.m_tiles_max;
     const int nt = blockIdx.x / g.m_tiles_max;
     int e, row0, row_end;
-    if (!find_m_tile(g.offsets, g.E, TM, mt, e, row0, row_end)) return;
+    if (!find_m_tile(g.offsets, g.E, g.P, TM, mt, e, row0, row_end)) return;
     const int n0 = nt * TN;
     const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
     float acc0[4][4] = {}, acc1[4][4] = {};
@@ -670,6 +711,7 @@ static int launch_simple(GemmArgs& g, hipStream_t st) {
 
 static int run_gemm(const moe_shape& s, GemmArgs& g, bool swiglu, hipStream_t st) {
     if (g.P == 0) return MOE_OK;
+    if (g.add0 && (!g.add1 || !g.row_map || !swiglu || s.act_dtype != MOE_BF16)) return MOE_ERR_INVALID;
     const int n_eff = g.N * (g.C1 ? 2 : 1);  // output columns of the launch
     bool dual = false, fast = s.act_dtype != MOE_F32;
     for (int i = 0; i < g.nseg; ++i) {
@@ -728,10 +770,20 @@ static int run_gemm(const moe_shape& s, GemmArgs& g, bool swiglu, hipStream_t st
     return launch_bf16<128, 128, 64, 64, 64, false, false>(g, st);
 }
 
-// scratch: h [P,F], then (rank > 0) tg, tu, td [P,r], all in the activation type
+// The per-token treatment of a shared base needs the deep bf16 kernels (every K a multiple of 64)
+// and pays only when a token has more than one expert.
+bool token_base_supported(const moe_shape& s) {
+    return (s.flags & MOE_FLAG_SHARED_BASE) && s.rank > 0 && s.top_k > 1 && s.act_dtype == MOE_BF16 &&
+           s.d_model % 64 == 0 && s.d_ff % 64 == 0 && s.rank % 64 == 0;
+}
+
+// scratch: h [P,F], then (rank > 0) tg, tu, td [P,r]; with a per-token shared base also the base
+// gate and up products and the gate-mixed h [T,F] each; all in the activation type
 size_t ffn_scratch_bytes(const moe_shape& s) {
     const size_t P = (size_t)s.n_tokens * s.top_k, es = elt_size(s.act_dtype);
-    return round_up(P * s.d_ff * es, 256) + 3 * round_up(P * s.rank * es, 256);
+    size_t n = round_up(P * s.d_ff * es, 256) + 3 * round_up(P * s.rank * es, 256);
+    if (token_base_supported(s)) n += 3 * round_up((size_t)s.n_tokens * s.d_ff * es, 256);
+    return n;
 }
 
 int launch_expert_ffn(const moe_shape& s, const moe_weights& w, const void* x,
@@ -787,6 +839,96 @@ int launch_expert_ffn(const moe_shape& s, const moe_weights& w, const void* x,
         if (base) g.seg[ns++] = GemmSeg{h, h, w.w_down, w.w_down, r == 0 ? (long long)d * F : 0, F, 0};
         if (r > 0) g.seg[ns++] = GemmSeg{td, td, w.ld, w.ld, (long long)d * r, r, 0};
         g.nseg = ns; g.N = d; g.C = y_perm;
+        if ((rc = run_gemm(s, g, false, st)) != MOE_OK) return rc;
+        stage_mark(timer, "gemm_down");
+    }
+    return MOE_OK;
+}
+
+// M_e = M0 + L_e R_e with M0 shared by all experts.  Per token t with experts e_j and gates g_j:
+//   gate/up:  M0 x_t is the same for every j, so it is computed once per token (a plain product
+//             over T rows) and added, per pair, to the low-rank term in the SwiGLU epilogue;
+//   down:     sum_j g_j M0 h_tj = M0 (sum_j g_j h_tj): the shared matrix meets the gate-mixed
+//             hidden vector once per token; the low-rank terms stay per pair and are mixed by
+//             the combine, which also adds the shared part.
+// This halves the base work at k = 2 (6 T d F flops instead of 6 P d F).
+int launch_expert_ffn_token_base(const moe_shape& s, const moe_weights& w, const void* x,
+                                 const int32_t* perm, const int32_t* inv_perm, const float* topk_gate,
+                                 const int32_t* offsets, void* y_perm, void* y_base, void* scratch,
+                                 hipStream_t st, StageTimer* timer) {
+    const int d = s.d_model, F = s.d_ff, r = s.rank, E = s.n_experts, T = s.n_tokens;
+    const int P = T * s.top_k;
+    if (P == 0) return MOE_OK;
+    const size_t es = elt_size(s.act_dtype);
+    char* sc = static_cast<char*>(scratch);
+    auto take = [&](size_t bytes) {
+        void* at = sc;
+        sc += round_up(bytes, 256);
+        return at;
+    };
+    void* h = take((size_t)P * F * es);
+    void* tg = take((size_t)P * r * es);
+    void* tu = take((size_t)P * r * es);
+    void* td = take((size_t)P * r * es);
+    void* bg = take((size_t)T * F * es);
+    void* bu = take((size_t)T * F * es);
+    void* z = take((size_t)T * F * es);
+    int rc;
+    auto grouped = [&]() {  // rows = pairs in expert order
+        GemmArgs g{};
+        g.offsets = offsets; g.row_map = perm; g.row_div = s.top_k; g.E = E; g.P = P;
+        return g;
+    };
+    auto per_token = [&]() {  // rows = tokens, one group, one matrix
+        GemmArgs g{};
+        g.offsets = nullptr; g.row_map = nullptr; g.row_div = 1; g.E = 1; g.P = T;
+        return g;
+    };
+    {  // tg = x R_g^T, tu = x R_u^T   [P, r]
+        GemmArgs g = grouped();
+        g.nseg = 1; g.N = r; g.C = tg; g.C1 = tu;
+        g.seg[0] = GemmSeg{x, x, w.rg, w.ru, (long long)r * d, d, 1};
+        if ((rc = run_gemm(s, g, false, st)) != MOE_OK) return rc;
+        stage_mark(timer, "gemm_rank_gate_up");
+    }
+    {  // bg = x M0_gate^T, bu = x M0_up^T   [T, F]
+        GemmArgs g = per_token();
+        g.nseg = 1; g.N = F; g.C = bg; g.C1 = bu;
+        g.seg[0] = GemmSeg{x, x, w.w_gate, w.w_up, 0, d, 0};
+        if ((rc = run_gemm(s, g, false, st)) != MOE_OK) return rc;
+        stage_mark(timer, "gemm_base_gate_up");
+    }
+    {  // h = silu(bg[t] + tg L_g^T) * (bu[t] + tu L_u^T)   [P, F]
+        GemmArgs g = grouped();
+        g.nseg = 1; g.N = F; g.C = h; g.add0 = bg; g.add1 = bu;
+        g.seg[0] = GemmSeg{tg, tu, w.lg, w.lu, (long long)F * r, r, 0};
+        if ((rc = run_gemm(s, g, true, st)) != MOE_OK) return rc;
+        stage_mark(timer, "gemm_gate_up_swiglu");
+    }
+    {  // td = h R_d^T   [P, r]
+        GemmArgs g = grouped();
+        g.nseg = 1; g.N = r; g.C = td;
+        g.seg[0] = GemmSeg{h, h, w.rd, w.rd, (long long)r * F, F, 0};
+        if ((rc = run_gemm(s, g, false, st)) != MOE_OK) return rc;
+        stage_mark(timer, "gemm_rank_down");
+    }
+    {  // z[t] = sum_j g_tj h[slot(t, j)]   [T, F]
+        moe_shape sm = s;
+        sm.d_model = F;
+        if ((rc = launch_combine(sm, h, inv_perm, topk_gate, nullptr, z, st)) != MOE_OK) return rc;
+        stage_mark(timer, "mix_hidden");
+    }
+    {  // y_base = z M0_down^T   [T, d]
+        GemmArgs g = per_token();
+        g.nseg = 1; g.N = d; g.C = y_base;
+        g.seg[0] = GemmSeg{z, z, w.w_down, w.w_down, 0, F, 0};
+        if ((rc = run_gemm(s, g, false, st)) != MOE_OK) return rc;
+        stage_mark(timer, "gemm_base_down");
+    }
+    {  // y_perm = td L_d^T   [P, d]
+        GemmArgs g = grouped();
+        g.nseg = 1; g.N = d; g.C = y_perm;
+        g.seg[0] = GemmSeg{td, td, w.ld, w.ld, (long long)d * r, r, 0};
         if ((rc = run_gemm(s, g, false, st)) != MOE_OK) return rc;
         stage_mark(timer, "gemm_down");
     }

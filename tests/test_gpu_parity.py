@@ -335,6 +335,16 @@ def test_forward_small_shapes_all_expert_kinds(dev, oracle):
                 _forward_case(dev, oracle, cfg, T, residual=(T == 7))
 
 
+@pytest.mark.parametrize("k,E,T", [(2, 8, 2), (2, 8, 37), (2, 8, 600), (3, 5, 150), (8, 8, 64), (2, 16, 9)])
+def test_forward_shared_base_once_per_token(dev, oracle, k, E, T):
+    # shapes whose widths are multiples of 64 take the path that applies the shared base once per
+    # token (plain products over T rows, low-rank terms per pair, the shared down term added in
+    # the combine); T = 9 with 16 experts leaves most groups empty, T = 600 spans several tiles
+    cfg = _cfg(name=f"tb{k}{E}", d=256, F=448, E=E, k=k, dtype="bf16", seed=900 + k + E, r=64,
+               base=True, std=0.05)
+    _forward_case(dev, oracle, cfg, T, residual=(T == 37))
+
+
 def test_forward_is_deterministic_and_matches_the_staged_calls(dev, oracle):
     cfg = wl.shrink(wl.CONFIGS["wearables"], d_model=512, d_ff=1024)
     w_np = wl.make_layer_weights(cfg)
