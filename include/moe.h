@@ -150,6 +150,10 @@ MOE_API int moe_combine(const moe_shape* shape, const void* y_perm, const int32_
  * Whole layer: route -> dispatch -> expert FFN -> combine in one call, free to fuse
  * stages (single-token decode streams only the selected experts' weights as a
  * bandwidth-bound matrix-vector product; larger T runs a grouped MFMA GEMM).
+ * With a shared base (Sec. 2.2, M_e = M0 + L_e R_e) and k > 1 the shared matrices are
+ * applied once per token, not once per (token, expert) pair: M0 x_t serves all of the
+ * token's experts, and sum_j g_j M0 h_j = M0 (sum_j g_j h_j); the result equals the staged
+ * calls' within the bf16 tolerance, not bit for bit.
  * topk_idx / topk_gate ([T,k]) are optional outputs (NULL to skip) and equal what
  * moe_route returns.  With MOE_FLAG_RESIDUAL, y = x + layer(x); y must not alias x.
  */
