@@ -320,8 +320,9 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(c
 // groups' accumulators meet in LDS at the end, added in group order.  This is for products
 // with fewer tiles than CUs and a long K, where the serial chain of k-steps of a single
 // tile, not the chip's throughput, sets the time.  Needs K % (KG * BK) == 0.
-template <int BM, int BN, int BK, int WM, int WN, bool SWIGLU, bool DUAL_A, int NS, int KG>
+template <int BM, int BN, int BK, int WM, int WN, bool SWIGLU, bool DUAL_A, int NS, int KG, bool ADD = false>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KG) void gemm_bf16_deep_kernel(const GemmArgs g) {
+    static_assert(!ADD || SWIGLU, "per-token addends belong to the SwiGLU epilogue");
     constexpr int WAVES_N = BN / WN;
     constexpr int NTHR = (BM / WM) * WAVES_N * 64;  // threads of one k-group
     constexpr int MT = WM / 32, NT = WN / 32;
@@ -351,12 +352,40 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KG) void gemm_bf16_dee
     char* const gmem = smem + kg * (2 * STAGE);  // this group's two stages
 
     f32x16 acc[MT][NT];
+    if constexpr (ADD) {
+        // Per-token addends: the accumulators start from the token's rows of add0 / add1 instead
+        // of zero.  The gathers are issued here, ahead of the first tile loads and with every
+        // register still free, so their latency hides behind the pipeline's own start-up.
+        static_assert(KG == 1, "addends are added once");
+        const bf16_t* add0 = static_cast<const bf16_t*>(g.add0);
+        const bf16_t* add1 = static_cast<const bf16_t*>(g.add1);
 #pragma unroll
-    for (int mi = 0; mi < MT; ++mi)
+        for (int mi = 0; mi < MT; ++mi) {
+            int tok[16];
 #pragma unroll
-        for (int ni = 0; ni < NT; ++ni)
+            for (int i = 0; i < 16; ++i) {
+                const int row = min(row0 + wm * WM + mi * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3), row_end - 1);
+                tok[i] = min(max(g.row_map[row], 0), g.P - 1) / g.row_div;
+            }
 #pragma unroll
-            for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
+            for (int ni = 0; ni < NT / 2; ++ni) {
+                const int col = min(n0 + wn * (WN / 2) + ni * 32 + (lane & 31), g.N - 1);
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const size_t at = (size_t)tok[i] * g.N + col;
+                    acc[mi][ni][i] = (float)add0[at];
+                    acc[mi][ni + NT / 2][i] = (float)add1[at];
+                }
+            }
+        }
+    } else {
+#pragma unroll
+        for (int mi = 0; mi < MT; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NT; ++ni)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
+    }
 
     struct Regs {
         bf16x8 a[AI], a1[DUAL_A ? AI : 1], b[BI];
@@ -546,34 +575,6 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KG) void gemm_bf16_dee
         }
     }
 
-    // ---- per-token addends: all their loads are issued before the first output store, so that
-    //      none of them has to wait behind a store it might alias -----------------------------------
-    if constexpr (SWIGLU) {
-        if (g.add0) {
-            const bf16_t* add0 = static_cast<const bf16_t*>(g.add0);
-            const bf16_t* add1 = static_cast<const bf16_t*>(g.add1);
-#pragma unroll
-            for (int mi = 0; mi < MT; ++mi) {
-                int tok[16];
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int row = min(row0 + wm * WM + mi * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3), row_end - 1);
-                    tok[i] = min(max(g.row_map[row], 0), g.P - 1) / g.row_div;
-                }
-#pragma unroll
-                for (int ni = 0; ni < NT / 2; ++ni) {
-                    const int col = min(n0 + wn * (WN / 2) + ni * 32 + (lane & 31), g.N - 1);
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const size_t at = (size_t)tok[i] * g.N + col;
-                        acc[mi][ni][i] += (float)add0[at];
-                        acc[mi][ni + NT / 2][i] += (float)add1[at];
-                    }
-                }
-            }
-        }
-    }
-
     // ---- epilogue (accumulator layout as in gemm_bf16_kernel) -------------------------------------
     bf16_t* C = static_cast<bf16_t*>(second ? g.C1 : g.C);
 #pragma unroll
@@ -675,8 +676,9 @@ static int launch_bf16(GemmArgs& g, hipStream_t st) {
     return launch_status();
 }
 
-template <int BM, int BN, int BK, int WM, int WN, bool SWIGLU, bool DUAL_A, int NS = 2, int KG = 1>
+template <int BM, int BN, int BK, int WM, int WN, bool SWIGLU, bool DUAL_A, int NS = 2, int KG = 1, bool ADD = false>
 static int launch_bf16_deep(GemmArgs& g, hipStream_t st) {
+    if ((g.add0 != nullptr) != ADD) return MOE_ERR_INVALID;
     constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;
     constexpr int NTHR = (BM / WM) * (BN / WN) * 64 * KG;
     static_assert(NTHR <= 1024, "workgroup size");
@@ -688,7 +690,7 @@ static int launch_bf16_deep(GemmArgs& g, hipStream_t st) {
     static_assert(lds <= 160 * 1024, "LDS stages exceed the CU's 160 KB");
     for (int i = 0; i < g.nseg; ++i)
         if (g.seg[i].K % (BK * KG) != 0) return MOE_ERR_UNSUPPORTED;  // callers check before choosing KG
-    auto kern = gemm_bf16_deep_kernel<BM, BN, BK, WM, WN, SWIGLU, DUAL_A, NS, KG>;
+    auto kern = gemm_bf16_deep_kernel<BM, BN, BK, WM, WN, SWIGLU, DUAL_A, NS, KG, ADD>;
     static bool attr_set = false;
     if (lds > 32 * 1024 && !attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -712,6 +714,8 @@ static int launch_simple(GemmArgs& g, hipStream_t st) {
 static int run_gemm(const moe_shape& s, GemmArgs& g, bool swiglu, hipStream_t st) {
     if (g.P == 0) return MOE_OK;
     if (g.add0 && (!g.add1 || !g.row_map || !swiglu || s.act_dtype != MOE_BF16)) return MOE_ERR_INVALID;
+    for (int i = 0; g.add0 && i < g.nseg; ++i)
+        if (g.seg[i].K % 64 != 0) return MOE_ERR_UNSUPPORTED;  // addends exist only in the deep kernels
     const int n_eff = g.N * (g.C1 ? 2 : 1);  // output columns of the launch
     bool dual = false, fast = s.act_dtype != MOE_F32;
     for (int i = 0; i < g.nseg; ++i) {
@@ -742,12 +746,16 @@ static int run_gemm(const moe_shape& s, GemmArgs& g, bool swiglu, hipStream_t st
         // long K two k-groups per workgroup (on 64 x 64 tiles when the groups average 32 rows or less).
         const long long big_tiles = (long long)(g.P / 256 + (g.E + 1) / 2) * ((n_eff + (swiglu ? 127 : 255)) / (swiglu ? 128 : 256));
         if (g.P >= 384 * g.E && big_tiles >= 400) {  // enough 256 x 256 tiles to fill 256 CUs
+            if (swiglu && g.add0) return launch_bf16_deep<256, 256, 32, 64, 128, true, true, 2, 1, true>(g, st);
             if (swiglu)
                 return dual ? launch_bf16_deep<256, 256, 32, 64, 128, true, true>(g, st)
                             : launch_bf16_deep<256, 256, 32, 64, 128, true, false>(g, st);
             return launch_bf16_deep<256, 256, 32, 64, 128, false, false>(g, st);
         }
         const bool small_groups = g.P <= 128 * g.E;
+        if (swiglu && g.add0)
+            return small_groups ? launch_bf16_deep<64, 128, 64, 32, 64, true, true, 2, 1, true>(g, st)
+                                : launch_bf16_deep<128, 128, 64, 64, 64, true, true, 2, 1, true>(g, st);
         if (swiglu) {
             if (small_groups)
                 return dual ? launch_bf16_deep<64, 128, 64, 32, 64, true, true>(g, st)
