@@ -38,6 +38,13 @@ __device__ __forceinline__ void static_for(F&& f) {
     static_for_impl(std::make_integer_sequence<int, N>{}, static_cast<F&&>(f));
 }
 
+// Products whose activation operand is the F-wide hidden tensor (down, rank-down): that operand is
+// as large as an expert's weights, so tiles are ordered in blocks of this many n-tiles with the
+// expert's m-tiles inside a block -- the workgroups in flight on an XCD then share a few A tiles
+// and a few B tiles instead of one B tile and every A tile (measured on the phone shape with
+// Zipf loads: down product 145 us with blocks of 8 or 16, 148 with 4, 153-157 with n-tile outer).
+constexpr int kHiddenOperandBlock = 8;
+
 struct GemmSeg {
     const void* A0;     // [*, K]
     const void* A1;     // A of the second accumulator (SWIGLU); may equal A0
@@ -65,6 +72,7 @@ struct GemmArgs {
     // (the token of sorted slot s is row_map[s] / row_div), [*, N] in the activation type, or NULL
     const void* add0;
     const void* add1;
+    int n_inner;        // tile order inside an expert: blocks of this many n-tiles (0 or 1: n-tile outer, m-tiles inner)
 };
 
 // Group e's row range; offsets == NULL means one group holding all P rows (a plain product).
@@ -83,7 +91,7 @@ __device__ __forceinline__ int group_end(const int32_t* __restrict__ offsets, in
 // bound (group sizes live on the device); surplus workgroups return false.
 __device__ __forceinline__ bool find_tile(const int32_t* __restrict__ offsets, int E, int P, int BM,
                                           int n_tiles, int& e_out, int& row0, int& row_end,
-                                          int& nt_out) {
+                                          int& nt_out, int n_inner = 0) {
     int total = 0;
     for (int e = 0; e < E; ++e)
         total += (group_end(offsets, e, P) - group_begin(offsets, e) + BM - 1) / BM;
@@ -101,8 +109,23 @@ __device__ __forceinline__ bool find_tile(const int32_t* __restrict__ offsets, i
         if (L < before + here) {
             const int local = L - before;
             e_out = e;
-            nt_out = local / mtiles;
-            row0 = prev + (local % mtiles) * BM;
+            // blocks of n_inner n-tiles: block outer, the expert's m-tiles in the middle, the
+            // block's n-tiles inner (n_inner = 1: n-tile outer, m-tiles inner)
+            const int nb = max(n_inner, 1);
+            const int full = (n_tiles / nb) * nb * mtiles;  // tiles in whole blocks
+            int mt, nt;
+            if (local < full) {
+                const int rem = local % (mtiles * nb);
+                mt = rem / nb;
+                nt = (local / (mtiles * nb)) * nb + rem % nb;
+            } else {
+                const int nb_tail = n_tiles % nb;
+                const int rem = local - full;
+                mt = rem / nb_tail;
+                nt = (n_tiles / nb) * nb + rem % nb_tail;
+            }
+            nt_out = nt;
+            row0 = prev + mt * BM;
             row_end = next;
             return true;
         }
@@ -164,7 +187,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(c
 
     // ---- which tile --------------------------------------------------------------------------
     int e, row0, row_end, nt;
-    if (!find_tile(g.offsets, g.E, g.P, BM, g.n_tiles, e, row0, row_end, nt)) return;
+    if (!find_tile(g.offsets, g.E, g.P, BM, g.n_tiles, e, row0, row_end, nt, g.n_inner)) return;
     constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;  // output columns per block
     const int n0 = nt * BN_OUT;
 
@@ -337,7 +360,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KG) void gemm_bf16_dee
     extern __shared__ __align__(16) char smem[];
 
     int e, row0, row_end, nt;
-    if (!find_tile(g.offsets, g.E, g.P, BM, g.n_tiles, e, row0, row_end, nt)) return;
+    if (!find_tile(g.offsets, g.E, g.P, BM, g.n_tiles, e, row0, row_end, nt, g.n_inner)) return;
     constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;
     // two plain products in one launch: the upper half of the n-tiles belongs to (A1, B1, C1)
     const bool second = !SWIGLU && g.C1 != nullptr && nt >= g.n_tiles / 2;
@@ -836,7 +859,7 @@ int launch_expert_ffn(const moe_shape& s, const moe_weights& w, const void* x,
     }
     if (r > 0) {  // td = h R_d^T   [P, r]
         GemmArgs g = fresh();
-        g.nseg = 1; g.N = r; g.C = td;
+        g.nseg = 1; g.N = r; g.C = td; g.n_inner = kHiddenOperandBlock;
         g.seg[0] = GemmSeg{h, h, w.rd, w.rd, (long long)r * F, F, 0};
         if ((rc = run_gemm(s, g, false, st)) != MOE_OK) return rc;
         stage_mark(timer, "gemm_rank_down");
@@ -846,7 +869,7 @@ int launch_expert_ffn(const moe_shape& s, const moe_weights& w, const void* x,
         int ns = 0;
         if (base) g.seg[ns++] = GemmSeg{h, h, w.w_down, w.w_down, r == 0 ? (long long)d * F : 0, F, 0};
         if (r > 0) g.seg[ns++] = GemmSeg{td, td, w.ld, w.ld, (long long)d * r, r, 0};
-        g.nseg = ns; g.N = d; g.C = y_perm;
+        g.nseg = ns; g.N = d; g.C = y_perm; g.n_inner = kHiddenOperandBlock;
         if ((rc = run_gemm(s, g, false, st)) != MOE_OK) return rc;
         stage_mark(timer, "gemm_down");
     }
@@ -915,7 +938,7 @@ int launch_expert_ffn_token_base(const moe_shape& s, const moe_weights& w, const
     }
     {  // td = h R_d^T   [P, r]
         GemmArgs g = grouped();
-        g.nseg = 1; g.N = r; g.C = td;
+        g.nseg = 1; g.N = r; g.C = td; g.n_inner = kHiddenOperandBlock;
         g.seg[0] = GemmSeg{h, h, w.rd, w.rd, (long long)r * F, F, 0};
         if ((rc = run_gemm(s, g, false, st)) != MOE_OK) return rc;
         stage_mark(timer, "gemm_rank_down");
@@ -928,7 +951,7 @@ int launch_expert_ffn_token_base(const moe_shape& s, const moe_weights& w, const
     }
     {  // y_base = z M0_down^T   [T, d]
         GemmArgs g = per_token();
-        g.nseg = 1; g.N = d; g.C = y_base;
+        g.nseg = 1; g.N = d; g.C = y_base; g.n_inner = kHiddenOperandBlock;
         g.seg[0] = GemmSeg{z, z, w.w_down, w.w_down, 0, F, 0};
         if ((rc = run_gemm(s, g, false, st)) != MOE_OK) return rc;
         stage_mark(timer, "gemm_base_down");
