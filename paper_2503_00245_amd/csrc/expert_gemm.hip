@@ -73,6 +73,8 @@ struct GemmArgs {
     const void* add0;
     const void* add1;
     int n_inner;        // tile order inside an expert: blocks of this many n-tiles (0 or 1: n-tile outer, m-tiles inner)
+    int split_slots;    // workgroups one XCD runs at a time; > 0: the tiles of its last, partial round are cut
+                        // into upper and lower halves when both halves still fit in one round (set by the launcher)
 };
 
 // Group e's row range; offsets == NULL means one group holding all P rows (a plain product).
@@ -89,17 +91,35 @@ __device__ __forceinline__ int group_end(const int32_t* __restrict__ offsets, in
 // takes the x-th contiguous eighth of that order, which keeps each XCD's L2 working set to
 // about one expert's rows plus the weight tiles it is streaming.  The grid is an upper
 // bound (group sizes live on the device); surplus workgroups return false.
+//
+// Tail split: an XCD runs split_slots workgroups at a time, so its tiles take
+// ceil(tiles / split_slots) rounds and the last round may be nearly empty.  When that last
+// round holds at most split_slots / 2 tiles, each of them is cut into an upper and a lower half
+// (BM / 2 rows) handled by two workgroups: the halves still fit in one round and each is
+// shorter than a whole tile (it fills half the activation rows and multiplies half the blocks).
 __device__ __forceinline__ bool find_tile(const int32_t* __restrict__ offsets, int E, int P, int BM,
                                           int n_tiles, int& e_out, int& row0, int& row_end,
-                                          int& nt_out, int n_inner = 0) {
+                                          int& nt_out, int n_inner = 0, int split_slots = 0) {
     int total = 0;
     for (int e = 0; e < E; ++e)
         total += (group_end(offsets, e, P) - group_begin(offsets, e) + BM - 1) / BM;
     total *= n_tiles;
     const int per_xcd = (total + 7) / 8;
     const int slot = blockIdx.x >> 3;
-    const int L = (blockIdx.x & 7) * per_xcd + slot;
-    if (slot >= per_xcd || L >= total) return false;
+    const int first = (blockIdx.x & 7) * per_xcd;               // this XCD's first tile
+    const int mine = max(0, min(per_xcd, total - first));       // and how many it has
+    int local_tile = slot, half = -1;
+    if (split_slots > 0) {
+        const int whole = (mine / split_slots) * split_slots;   // tiles in full rounds
+        const int rem = mine - whole;
+        if (rem > 0 && 2 * rem <= split_slots && slot >= whole) {
+            const int idx = slot - whole;
+            local_tile = whole + idx / 2;
+            half = idx & 1;
+        }
+    }
+    if (local_tile >= mine) return false;
+    const int L = first + local_tile;
     int before = 0;
     int prev = group_begin(offsets, 0);
     for (int e = 0; e < E; ++e) {
@@ -127,6 +147,11 @@ __device__ __forceinline__ bool find_tile(const int32_t* __restrict__ offsets, i
             nt_out = nt;
             row0 = prev + mt * BM;
             row_end = next;
+            if (half >= 0) {
+                row0 += half * (BM / 2);
+                row_end = min(next, row0 + BM / 2);
+                if (row0 >= row_end) return false;  // the tile had no rows in its lower half
+            }
             return true;
         }
         before += here;
@@ -187,7 +212,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(c
 
     // ---- which tile --------------------------------------------------------------------------
     int e, row0, row_end, nt;
-    if (!find_tile(g.offsets, g.E, g.P, BM, g.n_tiles, e, row0, row_end, nt, g.n_inner)) return;
+    if (!find_tile(g.offsets, g.E, g.P, BM, g.n_tiles, e, row0, row_end, nt, g.n_inner, g.split_slots)) return;
     constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;  // output columns per block
     const int n0 = nt * BN_OUT;
 
@@ -360,7 +385,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KG) void gemm_bf16_dee
     extern __shared__ __align__(16) char smem[];
 
     int e, row0, row_end, nt;
-    if (!find_tile(g.offsets, g.E, g.P, BM, g.n_tiles, e, row0, row_end, nt, g.n_inner)) return;
+    if (!find_tile(g.offsets, g.E, g.P, BM, g.n_tiles, e, row0, row_end, nt, g.n_inner, g.split_slots)) return;
     constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;
     // two plain products in one launch: the upper half of the n-tiles belongs to (A1, B1, C1)
     const bool second = !SWIGLU && g.C1 != nullptr && nt >= g.n_tiles / 2;
@@ -708,9 +733,15 @@ static int launch_bf16_deep(GemmArgs& g, hipStream_t st) {
     g.m_tiles_max = g.P / BM + g.E;
     g.n_tiles = (g.N + BN_OUT - 1) / BN_OUT * ((!SWIGLU && g.C1) ? 2 : 1);
     const int total = g.m_tiles_max * g.n_tiles;
-    const int grid = (total + 7) / 8 * 8;
     constexpr size_t lds = KG * 2 * ((size_t)BM * BK * 2 * (DUAL_A ? 2 : 1) + (size_t)BN * BK * 2);
     static_assert(lds <= 160 * 1024, "LDS stages exceed the CU's 160 KB");
+    // workgroups of this kernel that one XCD (32 CUs) holds at a time: bounded by LDS and, for
+    // these tiles (64 or more accumulator registers per lane), by two waves per SIMD; halves of
+    // BM / 2 rows only make sense when each wave's rows fall in one half
+    constexpr int kByLds = (int)((160 * 1024) / lds), kByWaves = 512 / NTHR;
+    constexpr int kPerCU = kByLds < kByWaves ? kByLds : kByWaves;
+    g.split_slots = (BM / 2) % WM == 0 && BM >= 128 && kPerCU >= 1 ? 32 * kPerCU : 0;
+    const int grid = ((total + 7) / 8 + g.split_slots / 2) * 8;
     for (int i = 0; i < g.nseg; ++i)
         if (g.seg[i].K % (BK * KG) != 0) return MOE_ERR_UNSUPPORTED;  // callers check before choosing KG
     auto kern = gemm_bf16_deep_kernel<BM, BN, BK, WM, WN, SWIGLU, DUAL_A, NS, KG, ADD>;
