@@ -207,6 +207,9 @@ def test_expert_ffn_tiny_fp32(dev, oracle):
     (256, 384, [0, 130, 130, 257, 300]),          # several m-tiles, an empty expert, ragged tails
     (200, 328, [0, 1, 3, 70, 71]),                # K and N not multiples of the tile, tiny groups
     (1024, 2816, [0, 64, 200, 200, 333, 333, 400, 401, 520]),  # wearables widths, 8 experts
+    # 585 gate/up tiles of 256 x 256: 74 (or 67) per XCD = two rounds of 32 and a thin third one, whose
+    # tiles are cut into upper and lower halves; the cut tiles include ragged ones (164 and 120 live rows)
+    (128, 5760, [0, 1700, 3100]),
 ])
 def test_expert_ffn_dense_bf16(dev, oracle, d, F, offsets):
     cfg = _cfg(d=d, F=F, E=len(offsets) - 1, dtype="bf16", seed=402 + d, std=0.05)
