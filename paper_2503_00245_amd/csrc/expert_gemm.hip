@@ -647,19 +647,39 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KG) void gemm_bf16_dee
     }
 
     // ---- epilogue (accumulator layout as in gemm_bf16_kernel) -------------------------------------
-    bf16_t* C = static_cast<bf16_t*>(second ? g.C1 : g.C);
+    // Offsets are 32-bit, relative to the tile's first output (a 64-bit multiply per element costs
+    // as much as the SiLU), and a 32-row block that lies wholly inside the group and the matrix
+    // stores without per-element predicates; a block with no rows of the group is skipped.
+    bf16_t* const Ct = static_cast<bf16_t*>(second ? g.C1 : g.C) + (size_t)row0 * g.N + n0;  // wave-uniform
+    const unsigned ldc = (unsigned)g.N;
+    const unsigned lane_off = (unsigned)((lane >> 5) * 4) * ldc + (unsigned)(lane & 31);
+    const bool cols_inside = n0 + BN_OUT <= g.N;
 #pragma unroll
     for (int mi = 0; mi < MT; ++mi) {
+        const int rb = wm * WM + mi * 32;             // the block's first row within the tile
+        const int rows_here = row_end - row0 - rb;    // rows of the group from there on (wave-uniform)
+        if (rows_here <= 0) continue;
 #pragma unroll
         for (int ni = 0; ni < (SWIGLU ? NT / 2 : NT); ++ni) {
-            const int col = n0 + wn * (SWIGLU ? WN / 2 : WN) + ni * 32 + (lane & 31);
+            const int cb = wn * (SWIGLU ? WN / 2 : WN) + ni * 32;
+            const unsigned base = lane_off + (unsigned)rb * ldc + (unsigned)cb;
+            if (rows_here >= 32 && cols_inside) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int row = row0 + wm * WM + mi * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
-                if (row < row_end && col < g.N) {
+                for (int i = 0; i < 16; ++i) {
                     float v = acc[mi][ni][i];
                     if (SWIGLU) v = silu_f32(v) * acc[mi][ni + NT / 2][i];
-                    C[(size_t)row * g.N + col] = (bf16_t)v;
+                    Ct[base + (unsigned)((i >> 2) * 8 + (i & 3)) * ldc] = (bf16_t)v;
+                }
+            } else {
+                const bool col_ok = n0 + cb + (lane & 31) < g.N;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int rr = (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
+                    if (rr < rows_here && col_ok) {
+                        float v = acc[mi][ni][i];
+                        if (SWIGLU) v = silu_f32(v) * acc[mi][ni + NT / 2][i];
+                        Ct[base + (unsigned)((i >> 2) * 8 + (i & 3)) * ldc] = (bf16_t)v;
+                    }
                 }
             }
         }
