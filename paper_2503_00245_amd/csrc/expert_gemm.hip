@@ -475,10 +475,19 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KG) void gemm_bf16_dee
         const bf16_t* pa[AI];
         const bf16_t* pa1[DUAL_A ? AI : 1];
         const bf16_t* pb[BI];
+        // (the row-map lookups of all of a thread's rows are issued together: one latency, not AI)
+        int arow[AI];
+#pragma unroll
+        for (int i = 0; i < AI; ++i) arow[i] = min(row0 + ld_row + RPP * i, row_end - 1);
+        if (sg.gather) {
+#pragma unroll
+            for (int i = 0; i < AI; ++i) arow[i] = g.row_map[arow[i]];
+#pragma unroll
+            for (int i = 0; i < AI; ++i) arow[i] = min(max(arow[i], 0), g.P - 1) / g.row_div;
+        }
 #pragma unroll
         for (int i = 0; i < AI; ++i) {
-            const int s = min(row0 + ld_row + RPP * i, row_end - 1);
-            const size_t off = (size_t)src_row(g, sg, s) * K + k_begin + ld_chunk * 8;
+            const size_t off = (size_t)arow[i] * K + k_begin + ld_chunk * 8;
             pa[i] = static_cast<const bf16_t*>(second ? sg.A1 : sg.A0) + off;
             if (DUAL_A) pa1[i] = static_cast<const bf16_t*>(sg.A1) + off;
         }
@@ -555,9 +564,9 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KG) void gemm_bf16_dee
         // tile kt+1 never also waits for the younger loads behind it.
         constexpr int UNR = (NS % 2 == 0) ? NS : 2 * NS;  // steps until (set, stage) repeat
         Regs r[NS];
-        __syncthreads();  // the previous segment's readers are done with both stages
 #pragma unroll
         for (int q = 0; q < NS; ++q) gload(r[q], min(q * BK, k_last));
+        __syncthreads();  // the previous segment's readers are done with both stages
         lstore(0, r[0]);
         __syncthreads();
         // Issue order inside a step: the step's global loads and LDS writes are spread through
