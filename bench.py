@@ -56,6 +56,14 @@ WORKLOADS = {
     "phone_wd_base_prefill": ("phone_wd_base", 2048),
     "phone_wd_base_decode": ("phone_wd_base", 1),
     "phone_stack_decode": ("phone_stack", 1),
+    "paper_phone_prefill": ("paper_phone", 2048),
+    "paper_phone_decode": ("paper_phone", 1),
+    "paper_wearables_prefill": ("paper_wearables", 2048),
+    "paper_wearables_decode": ("paper_wearables", 1),
+    "paper_phone_wd_prefill": ("paper_phone_wd", 2048),
+    "paper_phone_wd_decode": ("paper_phone_wd", 1),
+    "paper_wearables_wd_prefill": ("paper_wearables_wd", 2048),
+    "paper_wearables_wd_decode": ("paper_wearables_wd", 1),
 }
 
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of

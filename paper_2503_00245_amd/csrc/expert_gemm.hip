@@ -12,9 +12,8 @@
 //
 // bf16 kernels: block tile BM x BN x BK on (BM / WM) * (BN / WN) waves, wave tile WM x WN built
 // from v_mfma_f32_32x32x16_bf16, fp32 accumulators in registers.  Global -> registers -> LDS
-// with two LDS stages; the fast path (gemm_bf16_deep_kernel, K a multiple of BK) keeps a
-// second register set so that three tiles are in flight, the fallback (gemm_bf16_kernel)
-// zero-fills ragged K.  LDS rows are BK bf16 wide with the 16-byte chunk index XOR-ed by a
+// with two LDS stages and two register sets, so that three tiles are in flight; a K that is
+// not a multiple of BK (any multiple of 8) ends in a partly zero-filled step.  LDS rows are BK bf16 wide with the 16-byte chunk index XOR-ed by a
 // function of the row, which spreads both the row-wise fills and the column-of-rows MFMA
 // operand reads over all banks.  Tiles are enumerated expert-major, then n-tile, then the
 // expert's m-tiles, and the workgroup id is remapped so that each XCD walks a contiguous
@@ -219,166 +218,9 @@ __device__ __forceinline__ int lds_off(int row, int chunk) {
     return row * (BK * 2) + ((chunk ^ ((row / (16 / CPR)) % CPR)) << 4);
 }
 
-template <int BM, int BN, int BK, int WM, int WN, bool SWIGLU, bool DUAL_A>
-__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(const GemmArgs g) {
-    constexpr int WAVES_N = BN / WN;
-    constexpr int NTHR = (BM / WM) * WAVES_N * 64;
-    constexpr int MT = WM / 32, NT = WN / 32;
-    static_assert(!SWIGLU || NT % 2 == 0, "gate and up fragments pair up");
-    constexpr int CPR = BK / 8;
-    constexpr int RPP = NTHR / CPR;            // tile rows filled per pass of the workgroup
-    static_assert(BM % RPP == 0 && BN % RPP == 0 && (BN / 2) % RPP == 0, "fill passes");
-    constexpr int AI = BM / RPP, BI = BN / RPP;  // 16-byte chunks per thread per tile
-    constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
-    constexpr int STAGE = A_BYTES * (DUAL_A ? 2 : 1) + B_BYTES;
-    extern __shared__ __align__(16) char smem[];
-
-    // ---- which tile --------------------------------------------------------------------------
-    int e, row0, row_end, nt;
-    if (!find_tile(g.offsets, g.E, g.P, BM, g.n_tiles, e, row0, row_end, nt, g.n_inner, g.split_slots)) return;
-    constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;  // output columns per block
-    const int n0 = nt * BN_OUT;
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-    const int ld_row = tid / CPR, ld_chunk = tid % CPR;
-
-    f32x16 acc[MT][NT];
-#pragma unroll
-    for (int mi = 0; mi < MT; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < NT; ++ni)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
-
-    for (int sidx = 0; sidx < g.nseg; ++sidx) {
-        const GemmSeg& sg = g.seg[sidx];
-        const int K = sg.K;
-        const bool dual = DUAL_A && sg.A1 != sg.A0;
-        const bf16_t* A0 = static_cast<const bf16_t*>(sg.A0);
-        const bf16_t* A1 = static_cast<const bf16_t*>(sg.A1);
-        const bf16_t* B0 = static_cast<const bf16_t*>(sg.B0) + (size_t)e * sg.strideB;
-        const bf16_t* B1 = SWIGLU ? static_cast<const bf16_t*>(sg.B1) + (size_t)e * sg.strideB : B0;
-
-        // element offsets of this thread's rows (-1: outside the group / matrix -> zeros)
-        long long aoff[AI], boff[BI];
-#pragma unroll
-        for (int i = 0; i < AI; ++i) {
-            const int s = row0 + ld_row + RPP * i;
-            aoff[i] = s < row_end ? (long long)src_row(g, sg, s) * K : -1;
-        }
-#pragma unroll
-        for (int i = 0; i < BI; ++i) {
-            const int j = ld_row + RPP * i;
-            const int n = SWIGLU ? n0 + (j % (BN / 2)) : n0 + j;
-            boff[i] = n < g.N ? (long long)n * K : -1;
-        }
-
-        bf16x8 ra[AI], ra1[DUAL_A ? AI : 1], rb[BI];
-        auto load_tile = [&](int k0) {
-            const int kk = k0 + ld_chunk * 8;
-            const bool kin = kk < K;
-#pragma unroll
-            for (int i = 0; i < AI; ++i) {
-                ra[i] = bf16x8{};
-                if (kin && aoff[i] >= 0) ra[i] = *reinterpret_cast<const bf16x8*>(A0 + aoff[i] + kk);
-                if (DUAL_A) {
-                    ra1[i] = bf16x8{};
-                    if (dual && kin && aoff[i] >= 0)
-                        ra1[i] = *reinterpret_cast<const bf16x8*>(A1 + aoff[i] + kk);
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < BI; ++i) {
-                rb[i] = bf16x8{};
-                const bf16_t* B = (SWIGLU && i >= BI / 2) ? B1 : B0;
-                if (kin && boff[i] >= 0) rb[i] = *reinterpret_cast<const bf16x8*>(B + boff[i] + kk);
-            }
-        };
-        auto store_tile = [&](int stage) {
-            char* base = smem + stage * STAGE;
-#pragma unroll
-            for (int i = 0; i < AI; ++i) {
-                *reinterpret_cast<bf16x8*>(base + lds_off<BK>(ld_row + RPP * i, ld_chunk)) = ra[i];
-                if (DUAL_A && dual)
-                    *reinterpret_cast<bf16x8*>(base + A_BYTES + lds_off<BK>(ld_row + RPP * i, ld_chunk)) = ra1[i];
-            }
-            char* bb = base + A_BYTES * (DUAL_A ? 2 : 1);
-#pragma unroll
-            for (int i = 0; i < BI; ++i)
-                *reinterpret_cast<bf16x8*>(bb + lds_off<BK>(ld_row + RPP * i, ld_chunk)) = rb[i];
-        };
-
-        const int nk = (K + BK - 1) / BK;
-        __syncthreads();  // previous segment's readers are done with both stages
-        load_tile(0);
-        store_tile(0);
-        __syncthreads();
-        for (int kt = 0; kt < nk; ++kt) {
-            const int stage = kt & 1;
-            if (kt + 1 < nk) load_tile((kt + 1) * BK);
-            const char* base = smem + stage * STAGE;
-            const char* a0b = base;
-            const char* a1b = (DUAL_A && dual) ? base + A_BYTES : base;
-            const char* bb = base + A_BYTES * (DUAL_A ? 2 : 1);
-#pragma unroll
-            for (int ks = 0; ks < BK / 16; ++ks) {
-                const int chunk = ks * 2 + (lane >> 5);
-                bf16x8 fa[MT], fa1[DUAL_A ? MT : 1], fb[NT];
-#pragma unroll
-                for (int mi = 0; mi < MT; ++mi) {
-                    const int r = wm * WM + mi * 32 + (lane & 31);
-                    fa[mi] = *reinterpret_cast<const bf16x8*>(a0b + lds_off<BK>(r, chunk));
-                    if (DUAL_A) fa1[mi] = *reinterpret_cast<const bf16x8*>(a1b + lds_off<BK>(r, chunk));
-                }
-#pragma unroll
-                for (int ni = 0; ni < NT; ++ni) {
-                    int r;
-                    if (SWIGLU)
-                        r = (ni < NT / 2 ? 0 : BN / 2) + wn * (WN / 2) + (ni % (NT / 2)) * 32 + (lane & 31);
-                    else
-                        r = wn * WN + ni * 32 + (lane & 31);
-                    fb[ni] = *reinterpret_cast<const bf16x8*>(bb + lds_off<BK>(r, chunk));
-                }
-#pragma unroll
-                for (int mi = 0; mi < MT; ++mi)
-#pragma unroll
-                    for (int ni = 0; ni < NT; ++ni) {
-                        const bf16x8 av = (DUAL_A && SWIGLU && ni >= NT / 2) ? fa1[mi] : fa[mi];
-                        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, fb[ni], acc[mi][ni], 0, 0, 0);
-                    }
-            }
-            if (kt + 1 < nk) store_tile(stage ^ 1);
-            __syncthreads();
-        }
-    }
-
-    // ---- epilogue: accumulator element i of a 32x32 block sits at
-    //      row (i/4)*8 + (lane/32)*4 + i%4, column lane%32 ---------------------------------------
-    bf16_t* C = static_cast<bf16_t*>(g.C);
-#pragma unroll
-    for (int mi = 0; mi < MT; ++mi) {
-#pragma unroll
-        for (int ni = 0; ni < (SWIGLU ? NT / 2 : NT); ++ni) {
-            const int col = n0 + wn * (SWIGLU ? WN / 2 : WN) + ni * 32 + (lane & 31);
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int row = row0 + wm * WM + mi * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
-                if (row < row_end && col < g.N) {
-                    float v = acc[mi][ni][i];
-                    if (SWIGLU) v = silu_f32(v) * acc[mi][ni + NT / 2][i];
-                    C[(size_t)row * g.N + col] = (bf16_t)v;
-                }
-            }
-        }
-    }
-}
-
 // ============================================================================= bf16 MFMA, deep pipeline
-// Fast path for K multiples of BK.  Same tiling and swizzled LDS layout as
-// gemm_bf16_kernel, but with two register sets and two LDS stages, so three tiles are in
-// flight: tile kt is multiplied out of LDS while tile kt+1 waits in registers to be
+// K a multiple of 8 (rows are read in 16-byte chunks).  Two register sets and two LDS stages, so
+// three tiles are in flight: tile kt is multiplied out of LDS while tile kt+1 waits in registers to be
 // written to the other LDS stage at the end of the step and tile kt+2 is being fetched.
 // That puts two full steps of MFMA work between issuing a global load and first needing
 // its data.  Loads are unconditional (rows past the end of a group / matrix are clamped to
@@ -391,9 +233,14 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(c
 // groups' accumulators meet in LDS at the end, added in group order.  This is for products
 // with fewer tiles than CUs and a long K, where the serial chain of k-steps of a single
 // tile, not the chip's throughput, sets the time.  Needs K % (KG * BK) == 0.
-template <int BM, int BN, int BK, int WM, int WN, bool SWIGLU, bool DUAL_A, int NS, int KG, bool ADD = false>
+// TAIL: K need not be a multiple of BK (a separate instantiation, so that the loop of the common
+// case carries none of the tail's bookkeeping: with it the down product of a 2048 x 5632 layer
+// measured 3.5 % slower).
+template <int BM, int BN, int BK, int WM, int WN, bool SWIGLU, bool DUAL_A, int NS, int KG, bool ADD = false,
+          bool TAIL = false>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KG) void gemm_bf16_deep_kernel(const GemmArgs g) {
     static_assert(!ADD || SWIGLU, "per-token addends belong to the SwiGLU epilogue");
+    static_assert(!TAIL || KG == 1, "a K tail only without k-groups");
     constexpr int WAVES_N = BN / WN;
     constexpr int NTHR = (BM / WM) * WAVES_N * 64;  // threads of one k-group
     constexpr int MT = WM / 32, NT = WN / 32;
@@ -468,9 +315,16 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KG) void gemm_bf16_dee
         const bool dual = DUAL_A && sg.A1 != sg.A0;
         const bf16_t* B0 = static_cast<const bf16_t*>(second ? sg.B1 : sg.B0) + (size_t)e * sg.strideB;
         const bf16_t* B1 = SWIGLU ? static_cast<const bf16_t*>(sg.B1) + (size_t)e * sg.strideB : B0;
-        const int nk = K / (BK * KG);        // k-steps of this group (the same for every group)
+        const int nk = (K + BK * KG - 1) / (BK * KG);  // k-steps of this group (the same for every group)
         const int k_begin = kg * nk * BK;
         const int k_last = (nk - 1) * BK;    // relative to k_begin
+        // K tail (TAIL: K % BK != 0, a multiple of 8): in the last k-step a thread whose 16-byte
+        // chunk lies at or beyond K reads an earlier chunk of its row instead (in bounds) and zeroes
+        // its registers before they go to LDS.  Which threads those are never changes (a thread
+        // always loads the same chunk of a tile), so the loop pays one vector min per step.
+        const int tail_kt = (TAIL && K % BK != 0) ? nk - 1 : -1;               // wave-uniform
+        const bool tail_dead = TAIL && k_last + ld_chunk * 8 >= K;              // per thread
+        const int k_last_t = tail_dead ? max(k_last - BK, -(ld_chunk * 8)) : k_last;
 
         const bf16_t* pa[AI];
         const bf16_t* pa1[DUAL_A ? AI : 1];
@@ -507,6 +361,17 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KG) void gemm_bf16_dee
 #pragma unroll
             for (int i = 0; i < BI; ++i) r.b[i] = *reinterpret_cast<const bf16x8*>(pb[i] + k0);
         };
+        auto zero_dead = [&](Regs& r) {
+            if (tail_dead) {
+#pragma unroll
+                for (int i = 0; i < AI; ++i) {
+                    r.a[i] = bf16x8{};
+                    if (DUAL_A) r.a1[i] = bf16x8{};
+                }
+#pragma unroll
+                for (int i = 0; i < BI; ++i) r.b[i] = bf16x8{};
+            }
+        };
         auto lstore = [&](int stage, const Regs& r) {
             char* base = gmem + stage * STAGE;
 #pragma unroll
@@ -540,7 +405,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KG) void gemm_bf16_dee
 #pragma unroll
                 for (int ni = 0; ni < NT; ++ni) {
                     int r;
-                    if (SWIGLU)
+                    if constexpr (SWIGLU)
                         r = (ni < NT / 2 ? 0 : BN / 2) + wn * (WN / 2) + (ni % (NT / 2)) * 32 + (lane & 31);
                     else
                         r = wn * WN + ni * 32 + (lane & 31);
@@ -565,7 +430,10 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KG) void gemm_bf16_dee
         constexpr int UNR = (NS % 2 == 0) ? NS : 2 * NS;  // steps until (set, stage) repeat
         Regs r[NS];
 #pragma unroll
-        for (int q = 0; q < NS; ++q) gload(r[q], min(q * BK, k_last));
+        for (int q = 0; q < NS; ++q) gload(r[q], min(q * BK, k_last_t));
+        if constexpr (TAIL) {
+            if (tail_kt == 0) zero_dead(r[0]);
+        }
         __syncthreads();  // the previous segment's readers are done with both stages
         lstore(0, r[0]);
         __syncthreads();
@@ -602,7 +470,10 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KG) void gemm_bf16_dee
             // kt + 1 (set (S + 1) % NS) to the other stage
             auto step = [&](auto sc, int kt) {
                 constexpr int S = decltype(sc)::value;
-                gload(r[S % NS], min((kt + NS) * BK, k_last));
+                if constexpr (TAIL) {
+                    if (kt + 1 == tail_kt) zero_dead(r[(S + 1) % NS]);  // the tile this step writes to LDS
+                }
+                gload(r[S % NS], min((kt + NS) * BK, k_last_t));
                 if constexpr (MA > 0) compute(S & 1, ma);
                 lstore((S & 1) ^ 1, r[(S + 1) % NS]);
                 if constexpr (MA > 0) interleave(ma);
@@ -655,7 +526,8 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KG) void gemm_bf16_dee
         }
     }
 
-    // ---- epilogue (accumulator layout as in gemm_bf16_kernel) -------------------------------------
+    // ---- epilogue: accumulator element i of a 32x32 block sits at row (i/4)*8 + (lane/32)*4 + i%4,
+    //      column lane%32 -------------------------------------------------------------------------
     // Offsets are 32-bit, relative to the tile's first output (a 64-bit multiply per element costs
     // as much as the SiLU), and a 32-row block that lies wholly inside the group and the matrix
     // stores without per-element predicates; a block with no rows of the group is skipped.
@@ -755,27 +627,6 @@ __global__ __launch_bounds__(256) void gemm_simple_kernel(const GemmArgs g) {
 }
 
 // ============================================================================= host side
-template <int BM, int BN, int BK, int WM, int WN, bool SWIGLU, bool DUAL_A>
-static int launch_bf16(GemmArgs& g, hipStream_t st) {
-    constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;
-    constexpr int NTHR = (BM / WM) * (BN / WN) * 64;
-    g.m_tiles_max = g.P / BM + g.E;
-    g.n_tiles = (g.N + BN_OUT - 1) / BN_OUT;
-    const int total = g.m_tiles_max * g.n_tiles;
-    const int grid = (total + 7) / 8 * 8;
-    constexpr size_t lds = 2 * ((size_t)BM * BK * 2 * (DUAL_A ? 2 : 1) + (size_t)BN * BK * 2);
-    auto kern = gemm_bf16_kernel<BM, BN, BK, WM, WN, SWIGLU, DUAL_A>;
-    static bool attr_set = false;
-    if (lds > 32 * 1024 && !attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-            return MOE_ERR_LAUNCH;
-        attr_set = true;
-    }
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(NTHR), lds, st, g);
-    return launch_status();
-}
-
 template <int BM, int BN, int BK, int WM, int WN, bool SWIGLU, bool DUAL_A, int NS = 2, int KG = 1, bool ADD = false>
 static int launch_bf16_deep(GemmArgs& g, hipStream_t st) {
     if ((g.add0 != nullptr) != ADD) return MOE_ERR_INVALID;
@@ -798,18 +649,27 @@ static int launch_bf16_deep(GemmArgs& g, hipStream_t st) {
     // the whole weight tile, measured slower: down product at 512 tokens 94 us instead of 73)
     g.split_slots = (BM / 2) % WM == 0 && KG == 1 && kPerCU == 1 ? 32 : 0;
     const int grid = ((total + 7) / 8 + g.split_slots / 2) * 8;
-    for (int i = 0; i < g.nseg; ++i)
-        if (g.seg[i].K % (BK * KG) != 0) return MOE_ERR_UNSUPPORTED;  // callers check before choosing KG
-    auto kern = gemm_bf16_deep_kernel<BM, BN, BK, WM, WN, SWIGLU, DUAL_A, NS, KG, ADD>;
-    static bool attr_set = false;
-    if (lds > 32 * 1024 && !attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-            return MOE_ERR_LAUNCH;
-        attr_set = true;
+    bool tail = false;
+    for (int i = 0; i < g.nseg; ++i) {
+        const int K = g.seg[i].K;  // rows are read in 16-byte chunks; a K tail only without k-groups
+        if (K < 8 || K % 8 != 0 || (KG > 1 && K % (BK * KG) != 0)) return MOE_ERR_UNSUPPORTED;
+        tail |= K % BK != 0;
     }
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(NTHR), lds, st, g);
-    return launch_status();
+    static bool attr_set[2] = {false, false};
+    auto launch = [&](auto kern, int which) {
+        if (lds > 32 * 1024 && !attr_set[which]) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+                return (int)MOE_ERR_LAUNCH;
+            attr_set[which] = true;
+        }
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(NTHR), lds, st, g);
+        return launch_status();
+    };
+    if constexpr (KG == 1) {
+        if (tail) return launch(gemm_bf16_deep_kernel<BM, BN, BK, WM, WN, SWIGLU, DUAL_A, NS, KG, ADD, true>, 1);
+    }
+    return launch(gemm_bf16_deep_kernel<BM, BN, BK, WM, WN, SWIGLU, DUAL_A, NS, KG, ADD, false>, 0);
 }
 
 template <typename T, bool SWIGLU>
@@ -825,12 +685,12 @@ static int run_gemm(const moe_shape& s, GemmArgs& g, bool swiglu, hipStream_t st
     if (g.P == 0) return MOE_OK;
     if (g.add0 && (!g.add1 || !g.row_map || !swiglu || s.act_dtype != MOE_BF16)) return MOE_ERR_INVALID;
     for (int i = 0; g.add0 && i < g.nseg; ++i)
-        if (g.seg[i].K % 64 != 0) return MOE_ERR_UNSUPPORTED;  // addends exist only in the deep kernels
+        if (g.seg[i].K % 8 != 0) return MOE_ERR_UNSUPPORTED;  // addends exist only in the deep kernels
     const int n_eff = g.N * (g.C1 ? 2 : 1);  // output columns of the launch
     bool dual = false, fast = s.act_dtype != MOE_F32;
     for (int i = 0; i < g.nseg; ++i) {
         dual |= swiglu && g.seg[i].A1 != g.seg[i].A0;
-        fast &= g.seg[i].K % 64 == 0;  // the deep pipeline has no K tail
+        fast &= g.seg[i].K >= 8 && g.seg[i].K % 8 == 0;  // the deep pipeline reads 16-byte chunks
     }
     if (g.C1 && !fast) {  // only the deep kernel takes two products per launch: run them one by one
         GemmArgs second = g;
@@ -882,17 +742,15 @@ static int run_gemm(const moe_shape& s, GemmArgs& g, bool swiglu, hipStream_t st
         }
         return launch_bf16_deep<128, 128, 64, 64, 64, false, false>(g, st);
     }
-    if (swiglu)
-        return dual ? launch_bf16<128, 128, 64, 64, 64, true, true>(g, st)
-                    : launch_bf16<128, 128, 64, 64, 64, true, false>(g, st);
-    return launch_bf16<128, 128, 64, 64, 64, false, false>(g, st);
+    return MOE_ERR_UNSUPPORTED;  // bf16 rows that are not whole 16-byte chunks (the entry points reject them)
 }
 
-// The per-token treatment of a shared base needs the deep bf16 kernels (every K a multiple of 64)
-// and pays only when a token has more than one expert.
+// The per-token treatment of a shared base needs the deep bf16 kernels (every K a multiple of 8,
+// which the shape check of the entry points already demands) and pays only when a token has more
+// than one expert.
 bool token_base_supported(const moe_shape& s) {
     return (s.flags & MOE_FLAG_SHARED_BASE) && s.rank > 0 && s.top_k > 1 && s.act_dtype == MOE_BF16 &&
-           s.d_model % 64 == 0 && s.d_ff % 64 == 0 && s.rank % 64 == 0;
+           s.d_model % 8 == 0 && s.d_ff % 8 == 0 && s.rank % 8 == 0;
 }
 
 // scratch: h [P,F], then (rank > 0) tg, tu, td [P,r]; with a per-token shared base also the base

@@ -210,6 +210,11 @@ def test_expert_ffn_tiny_fp32(dev, oracle):
     # 585 gate/up tiles of 256 x 256: 74 (or 67) per XCD = two rounds of 32 and a thin third one, whose
     # tiles are cut into upper and lower halves; the cut tiles include ragged ones (164 and 120 live rows)
     (128, 5760, [0, 1700, 3100]),
+    # K tails in the 256-row kernel: K = 72 is two k-steps of 32 and a tail of 8; the down product
+    # then has K = 4008 (a tail of 40 in a 64-wide step)
+    (72, 4008, [0, 1700, 3100]),
+    # K shorter than one k-step: the only step is the tail
+    (24, 4104, [0, 1500, 3000]),
 ])
 def test_expert_ffn_dense_bf16(dev, oracle, d, F, offsets):
     cfg = _cfg(d=d, F=F, E=len(offsets) - 1, dtype="bf16", seed=402 + d, std=0.05)
@@ -340,12 +345,20 @@ def test_forward_small_shapes_all_expert_kinds(dev, oracle):
 
 @pytest.mark.parametrize("k,E,T", [(2, 8, 2), (2, 8, 37), (2, 8, 600), (3, 5, 150), (8, 8, 64), (2, 16, 9)])
 def test_forward_shared_base_once_per_token(dev, oracle, k, E, T):
-    # shapes whose widths are multiples of 64 take the path that applies the shared base once per
-    # token (plain products over T rows, low-rank terms per pair, the shared down term added in
-    # the combine); T = 9 with 16 experts leaves most groups empty, T = 600 spans several tiles
+    # bf16 layers with k > 1 take the path that applies the shared base once per token (plain
+    # products over T rows, low-rank terms per pair, the shared down term added in the combine);
+    # T = 9 with 16 experts leaves most groups empty, T = 600 spans several tiles
     cfg = _cfg(name=f"tb{k}{E}", d=256, F=448, E=E, k=k, dtype="bf16", seed=900 + k + E, r=64,
                base=True, std=0.05)
     _forward_case(dev, oracle, cfg, T, residual=(T == 37))
+
+
+@pytest.mark.parametrize("T", [5, 300, 1500])
+def test_forward_shared_base_once_per_token_ragged_widths(dev, oracle, T):
+    # the same path with widths that are multiples of 8 only: every product has a K tail
+    # (200 = 3 x 64 + 8, 328 = 5 x 64 + 8, rank 40 is shorter than one k-step)
+    cfg = _cfg(name="tbr", d=200, F=328, E=4, k=2, dtype="bf16", seed=931, r=40, base=True, std=0.05)
+    _forward_case(dev, oracle, cfg, T, sample=64)
 
 
 def test_forward_is_deterministic_and_matches_the_staged_calls(dev, oracle):
@@ -552,12 +565,14 @@ def test_stack_trace_feeds_the_trace_metrics(dev, oracle):
     (400, 1064, 200),    # wearable-sized WD row
 ])
 def test_forward_table1_shapes(dev, oracle, d, F, r):
-    # widths that are not multiples of the GEMM's K tile exercise the zero-filled-tail kernel
+    # widths that are not multiples of the GEMM's K tile exercise its K tail
     cfg = _cfg(name=f"t1_{d}", d=d, F=F, E=8, k=2, dtype="bf16", seed=600 + d, r=r, std=0.03)
     w_np = wl.make_layer_weights(cfg, with_bias=False)
     w_t = weights_to_device(w_np, dev)
     _forward_case(dev, oracle, cfg, 1, w_np, w_t)
     _forward_case(dev, oracle, cfg, 150, w_np, w_t, sample=24)
+    # a prefill batch: 512 rows per expert on average, the 256-row tiles with their K tails
+    _forward_case(dev, oracle, cfg, 2048, w_np, w_t, sample=12)
 
 
 @pytest.mark.parametrize("E", [2, 4, 8, 16])

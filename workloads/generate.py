@@ -61,6 +61,13 @@ CONFIGS: Dict[str, LayerConfig] = {
                                  rank=64, shared_base=True, wd_product_std=0.005),
     # 24 phone-shaped layers run back to back with residual adds
     "phone_stack": LayerConfig("phone_stack", 2048, 5632, 8, 2, "bf16", 245005, n_layers=24),
+    # The paper's own model rows (Table 1: hidden size per row; d_ff taken as 8/3 of it, rounded to
+    # a multiple of 8; 8 experts, 2 active as in Sec. 3.1).  Widths that are not multiples of 64.
+    "paper_phone": LayerConfig("paper_phone", 1440, 3840, 8, 2, "bf16", 245021),
+    "paper_wearables": LayerConfig("paper_wearables", 432, 1152, 8, 2, "bf16", 245022),
+    # weight-decomposed rows: rank = half the hidden size (Sec. 2.2)
+    "paper_phone_wd": LayerConfig("paper_phone_wd", 1600, 4264, 8, 2, "bf16", 245023, rank=800),
+    "paper_wearables_wd": LayerConfig("paper_wearables_wd", 400, 1064, 8, 2, "bf16", 245024, rank=200),
 }
 
 
