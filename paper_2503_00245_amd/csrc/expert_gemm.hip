@@ -528,11 +528,76 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KG) void gemm_bf16_dee
 
     // ---- epilogue: accumulator element i of a 32x32 block sits at row (i/4)*8 + (lane/32)*4 + i%4,
     //      column lane%32 -------------------------------------------------------------------------
-    // Offsets are 32-bit, relative to the tile's first output (a 64-bit multiply per element costs
-    // as much as the SiLU), and a 32-row block that lies wholly inside the group and the matrix
-    // stores without per-element predicates; a block with no rows of the group is skipped.
+    // A block with no rows of the group is skipped.
     bf16_t* const Ct = static_cast<bf16_t*>(second ? g.C1 : g.C) + (size_t)row0 * g.N + n0;  // wave-uniform
     const unsigned ldc = (unsigned)g.N;
+    if constexpr (KG == 1) {
+        // Through LDS, so that the tile leaves in 16-byte stores (8 per wave and 32 x 64 block)
+        // instead of one bf16 per lane and instruction (64 of them).  Each wave stages 32 rows x up
+        // to 64 columns at a time in a region of its own (every wave is past the k-loop's last
+        // barrier, so the tile stages are free; a wave's LDS operations complete in order, so no
+        // further barrier is needed): neighbouring lanes first swap half of their values so that
+        // a lane holds two adjacent columns of two rows, written as 32-bit words; then the rows
+        // are read back 16 bytes per lane.  Worth 0.5-1 % of a prefill step on the shapes measured.
+        constexpr int OC = SWIGLU ? WN / 2 : WN;   // output columns of a wave
+        constexpr int PW = OC < 64 ? OC : 64;      // columns staged per pass
+        constexpr int NB = PW / 32;
+        constexpr int PITCH = PW * 2 + 32;         // bytes per staged row (keeps the four lane groups of a write on distinct banks)
+        constexpr int REGION = 32 * PITCH;
+        static_assert(REGION * (NTHR / 64) <= 2 * STAGE, "the staging regions fit in the tile stages");
+        constexpr int LPR = PW / 8, RPI = 64 / LPR;  // lanes per staged row, rows per read instruction
+        char* const region = smem + wave * REGION;
+        const bool odd = lane & 1;
+        const int wr_row = (lane >> 5) * 4 + (odd ? 2 : 0);
+        const int wr_col = (lane & 30) * 2;        // byte offset of the column pair in a 32-column block
+        const int rd_row = lane / LPR, rd_chunk = lane % LPR;
+#pragma unroll
+        for (int mi = 0; mi < MT; ++mi) {
+            const int rb = wm * WM + mi * 32;           // the block's first row within the tile
+            const int rows_here = row_end - row0 - rb;  // rows of the group from there on (wave-uniform)
+            if (rows_here <= 0) continue;
+#pragma unroll
+            for (int cg = 0; cg < OC / PW; ++cg) {
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    const int ni = cg * NB + nb;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        float o[4];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            o[j] = acc[mi][ni][q * 4 + j];
+                            if (SWIGLU) o[j] = silu_f32(o[j]) * acc[mi][ni + NT / 2][q * 4 + j];
+                        }
+                        const bf16x2 t01 = {(bf16_t)o[0], (bf16_t)o[1]}, t23 = {(bf16_t)o[2], (bf16_t)o[3]};
+                        const unsigned p01 = __builtin_bit_cast(unsigned, t01);  // rows +0, +1 of my column
+                        const unsigned p23 = __builtin_bit_cast(unsigned, t23);  // rows +2, +3
+                        // even lanes keep rows +0, +1 and get them of the next column; odd lanes keep
+                        // rows +2, +3 and get them of the previous column
+                        const unsigned keep = odd ? p23 : p01;
+                        const unsigned recv = (unsigned)dpp_i32<kDppSwap1>((int)(odd ? p01 : p23));
+                        const unsigned lo = odd ? recv : keep, hi = odd ? keep : recv;  // even / odd column
+                        char* at = region + (q * 8 + wr_row) * PITCH + nb * 64 + wr_col;
+                        *reinterpret_cast<unsigned*>(at) = (lo & 0xffffu) | (hi << 16);
+                        *reinterpret_cast<unsigned*>(at + PITCH) = (lo >> 16) | (hi & 0xffff0000u);
+                    }
+                }
+                const int c0 = wn * OC + cg * PW + rd_chunk * 8;  // first of this lane's 8 columns within the tile
+#pragma unroll
+                for (int it = 0; it < 32 / RPI; ++it) {
+                    const int r = it * RPI + rd_row;
+                    const uint4 v = *reinterpret_cast<const uint4*>(region + r * PITCH + rd_chunk * 16);
+                    if (r < rows_here && n0 + c0 < g.N)
+                        *reinterpret_cast<uint4*>(Ct + (unsigned)(rb + r) * ldc + (unsigned)c0) = v;
+                }
+            }
+        }
+        return;
+    }
+    // Kernels with k-groups (small products) store straight from the accumulator layout.  Offsets
+    // are 32-bit, relative to the tile's first output (a 64-bit multiply per element costs as much
+    // as the SiLU), and a 32-row block that lies wholly inside the group and the matrix stores
+    // without per-element predicates.
     const unsigned lane_off = (unsigned)((lane >> 5) * 4) * ldc + (unsigned)(lane & 31);
     const bool cols_inside = n0 + BN_OUT <= g.N;
 #pragma unroll
