@@ -335,6 +335,19 @@ def main():
                  "algorithmic_flops": flops * n_l, "algorithmic_weight_bytes": wbytes * n_l,
                  "sum_of_stage_ms": round(sum(stages.values()), 5)}
 
+        # ---- what the router does with the timed inputs: share of the (token, slot) pairs per expert
+        # (first layer; for single-token steps over all the rotated input tokens) --------------------
+        xcat = torch.cat(xs[:min(n_inputs, max(1, 4096 // T))], dim=0)
+        n_routed = xcat.shape[0]
+        rshape = pkg.shape_for(layers_t[0], n_routed, cfg.top_k, pkg.MOE_BF16)
+        ridx = torch.empty((n_routed, cfg.top_k), dtype=torch.int32, device=dev)
+        rgate = torch.empty((n_routed, cfg.top_k), dtype=torch.float32, device=dev)
+        pkg.moe_route(rshape, xcat, layers_t[0]["router_w"], layers_t[0].get("router_b"), ridx, rgate)
+        torch.cuda.synchronize()
+        counts = np.bincount(ridx.cpu().numpy().ravel(), minlength=cfg.n_experts)
+        routing = {"tokens": int(n_routed), "expert_share": [round(float(c) / counts.sum(), 4) for c in counts]}
+        del xcat, ridx, rgate
+
         # ---- CPU oracle baseline on a bounded sample of the same workload -------------------------
         cpu = None
         if want_cpu:
@@ -382,7 +395,7 @@ def main():
                        "shared_base": cfg.shared_base, "n_layers": cfg.n_layers, "tokens_per_step": T,
                        "zipf_router_bias": bool(cfg.zipf), "weight_copies_rotated": len(copies)},
             "roofline": roofline, "cpu_baseline": cpu, "stages_ms": {k: round(v, 5) for k, v in stages.items()},
-            "layer": layer,
+            "layer": layer, "routing": routing,
             "latency_ms": latency, "graph_replay_ms_per_step": None if graph_ms is None else round(graph_ms, 5),
             "gpu_state": {"before": state_before, "after": state_after},
             "input_generation_s": round(gen_s, 1),
@@ -396,7 +409,7 @@ def main():
         # single-token decode (here, same layer, same process)
         d = run_workload("phone_decode", None, None, None, False)
         out["decode"] = {k: d[k] for k in ("ms_per_step", "value", "unit", "steps", "warmup", "roofline",
-                                           "stages_ms", "latency_ms", "graph_replay_ms_per_step")}
+                                           "stages_ms", "latency_ms", "graph_replay_ms_per_step", "routing")}
         out["decode"]["workload"] = "phone_decode"
         out["decode"]["layer_hbm_frac_of_peak"] = d["layer"]["hbm_frac_of_peak"]
         out["decode"]["weight_copies_rotated"] = d["config"]["weight_copies_rotated"]
