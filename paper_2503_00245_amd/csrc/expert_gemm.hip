@@ -778,7 +778,7 @@ static int run_gemm(const moe_shape& s, GemmArgs& g, bool swiglu, hipStream_t st
         // are bound by streaming the weights, and what counts is enough workgroups to pull them
         // with every CU: 128 x 128 x 64 tiles (two workgroups per CU), 64-row tiles once the
         // groups hold about 128 rows or fewer, and for a plain product with few tiles and a
-        // long K two k-groups per workgroup (on 64 x 64 tiles when the groups average 32 rows or less).
+        // long K two k-groups per workgroup (on 64 x 64 tiles when the groups average 24 rows or less: measured faster at 16, slower at 32).
         const long long big_tiles = (long long)(g.P / 256 + (g.E + 1) / 2) * ((n_eff + (swiglu ? 127 : 255)) / (swiglu ? 128 : 256));
         if (g.P >= 384 * g.E && big_tiles >= 400) {  // enough 256 x 256 tiles to fill 256 CUs
             if (swiglu && g.add0) return launch_bf16_deep<256, 256, 32, 64, 128, true, true, 2, 1, true>(g, st);
@@ -802,7 +802,7 @@ static int run_gemm(const moe_shape& s, GemmArgs& g, bool swiglu, hipStream_t st
         bool k_pairs = true;
         for (int i = 0; i < g.nseg; ++i) k_pairs &= g.seg[i].K % 128 == 0;
         if (tiles128 < 160 && k_pairs) {
-            if (g.P <= 32 * g.E) return launch_bf16_deep<64, 64, 64, 32, 32, false, false, 2, 2>(g, st);
+            if (g.P <= 24 * g.E) return launch_bf16_deep<64, 64, 64, 32, 32, false, false, 2, 2>(g, st);
             return launch_bf16_deep<64, 128, 64, 32, 64, false, false, 2, 2>(g, st);
         }
         return launch_bf16_deep<128, 128, 64, 64, 64, false, false>(g, st);
