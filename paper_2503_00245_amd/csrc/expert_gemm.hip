@@ -709,10 +709,12 @@ static int launch_bf16_deep(GemmArgs& g, hipStream_t st) {
     constexpr int kWavesPerSimd = (WM * WN / 64 >= 64) ? 2 : 3;  // by accumulator registers per lane
     constexpr int kByLds = (int)((160 * 1024) / lds), kByWaves = kWavesPerSimd * 256 / NTHR;
     constexpr int kPerCU = kByLds < kByWaves ? kByLds : kByWaves;
-    // (only for kernels that run one workgroup per CU: with two or three per CU the tiles of a
-    // thin last round already run faster than in a full one, and halves, which each still stream
-    // the whole weight tile, measured slower: down product at 512 tokens 94 us instead of 73)
-    g.split_slots = (BM / 2) % WM == 0 && KG == 1 && kPerCU == 1 ? 32 : 0;
+    // (for kernels that run one or two workgroups per CU.  It needs a full round before the thin
+    // one: with less than one round of tiles in all, halves -- which each still stream the whole
+    // weight tile -- measured slower, down product at 512 tokens 94 us instead of 73.  Cutting the
+    // halves once more along the columns, one wave of four left with work, was slower too:
+    // down product at 2048 tokens 152 us against 144.)
+    g.split_slots = (BM / 2) % WM == 0 && KG == 1 && kPerCU <= 2 ? 32 * kPerCU : 0;
     const int grid = ((total + 7) / 8 + g.split_slots / 2) * 8;
     bool tail = false;
     for (int i = 0; i < g.nseg; ++i) {

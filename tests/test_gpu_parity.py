@@ -210,6 +210,11 @@ def test_expert_ffn_tiny_fp32(dev, oracle):
     # 585 gate/up tiles of 256 x 256: 74 (or 67) per XCD = two rounds of 32 and a thin third one, whose
     # tiles are cut into upper and lower halves; the cut tiles include ragged ones (164 and 120 live rows)
     (128, 5760, [0, 1700, 3100]),
+    # 540 gate/up tiles of 256 x 256: 68 per XCD = two rounds and 4 tiles that are cut
+    (128, 5760, [0, 1700, 2900]),
+    # the same for a kernel that runs two workgroups per CU: 576 down tiles of 128 x 128, 72 per XCD =
+    # one round of 64 and 8 tiles cut into halves (the last tile of the second group holds 74 rows)
+    (2048, 192, [0, 2304, 4554]),
     # K tails in the 256-row kernel: K = 72 is two k-steps of 32 and a tail of 8; the down product
     # then has K = 4008 (a tail of 40 in a 64-wide step)
     (72, 4008, [0, 1700, 3100]),
