@@ -348,6 +348,36 @@ def main():
         routing = {"tokens": int(n_routed), "expert_share": [round(float(c) / counts.sum(), 4) for c in counts]}
         del xcat, ridx, rgate
 
+        # ---- the paper's offloading cost model (Sec. 3.4.2) restated on this routing: run the stack
+        # token by token, keep every layer's selection, count on the GPU how often a layer's
+        # expert set changes and how many experts the rule would bring in ------------------------
+        offload = None
+        if stack:
+            n_tr = min(steps, 256)
+            trace_tl = torch.empty((n_tr, cfg.n_layers, cfg.top_k), dtype=torch.int32, device=dev)
+            for i in range(n_tr):
+                pkg.moe_stack_forward(shape, w_structs[0], xs[i % n_inputs], y, trace_tl[i], ws)
+            trace = trace_tl.permute(1, 0, 2).contiguous()  # [layer, token, slot]
+            changes = torch.zeros(cfg.n_layers, dtype=torch.int64, device=dev)
+            loads = torch.zeros(cfg.n_layers, dtype=torch.int64, device=dev)
+            h_e = torch.zeros(cfg.n_experts, dtype=torch.int64, device=dev)
+            h_all = torch.zeros(1, dtype=torch.int64, device=dev)
+            pkg.moe_offload_counters(trace, cfg.n_experts, changes, loads)
+            pkg.moe_expert_replacements(trace, cfg.n_experts, h_e, h_all)
+            torch.cuda.synchronize()
+            expert_bytes = 3 * cfg.d_model * cfg.d_ff * 2
+            n_loads = int(loads.sum().item())
+            offload = {"tokens": n_tr, "layers": cfg.n_layers,
+                       "set_changes_per_token_and_layer": round(int(changes.sum().item()) / (n_tr * cfg.n_layers), 4),
+                       "experts_loaded_per_token": round(n_loads / n_tr, 3),
+                       "bytes_loaded_per_token": int(n_loads / n_tr * expert_bytes),
+                       "set_changes_first_and_last_layer": [round(int(changes[0].item()) / n_tr, 4),
+                                                            round(int(changes[-1].item()) / n_tr, 4)],
+                       "expert_replacements_half_H": int(h_all.item()) // 2,
+                       "note": "independent random tokens: the first layer routes them independently; deeper in "
+                               "this un-normalised residual stack the streams share a growing common part"}
+            del trace_tl, trace
+
         # ---- CPU oracle baseline on a bounded sample of the same workload -------------------------
         cpu = None
         if want_cpu:
@@ -395,7 +425,7 @@ def main():
                        "shared_base": cfg.shared_base, "n_layers": cfg.n_layers, "tokens_per_step": T,
                        "zipf_router_bias": bool(cfg.zipf), "weight_copies_rotated": len(copies)},
             "roofline": roofline, "cpu_baseline": cpu, "stages_ms": {k: round(v, 5) for k, v in stages.items()},
-            "layer": layer, "routing": routing,
+            "layer": layer, "routing": routing, "offload_model": offload,
             "latency_ms": latency, "graph_replay_ms_per_step": None if graph_ms is None else round(graph_ms, 5),
             "gpu_state": {"before": state_before, "after": state_after},
             "input_generation_s": round(gen_s, 1),
