@@ -342,11 +342,23 @@ def main():
         rshape = pkg.shape_for(layers_t[0], n_routed, cfg.top_k, pkg.MOE_BF16)
         ridx = torch.empty((n_routed, cfg.top_k), dtype=torch.int32, device=dev)
         rgate = torch.empty((n_routed, cfg.top_k), dtype=torch.float32, device=dev)
-        pkg.moe_route(rshape, xcat, layers_t[0]["router_w"], layers_t[0].get("router_b"), ridx, rgate)
+        rprobs = torch.empty((n_routed, cfg.n_experts), dtype=torch.float32, device=dev)
+        pkg.moe_route(rshape, xcat, layers_t[0]["router_w"], layers_t[0].get("router_b"), ridx, rgate, rprobs)
         torch.cuda.synchronize()
         counts = np.bincount(ridx.cpu().numpy().ravel(), minlength=cfg.n_experts)
         routing = {"tokens": int(n_routed), "expert_share": [round(float(c) / counts.sum(), 4) for c in counts]}
-        del xcat, ridx, rgate
+        if n_routed > 1:
+            # the same tokens read as one sequence: Eq. 4-7's replacement count and loss value
+            bles = torch.zeros(5, dtype=torch.float64, device=dev)
+            bws = torch.empty(max(1, pkg.moe_bles_workspace_bytes(1, n_routed, cfg.n_experts)),
+                              dtype=torch.uint8, device=dev)
+            pkg.moe_bles_loss(rprobs.view(1, n_routed, cfg.n_experts), ridx.view(1, n_routed, cfg.top_k), bles, bws)
+            torch.cuda.synchronize()
+            b = bles.cpu().numpy()
+            routing["as_one_sequence"] = {"H": int(b[0]), "H_norm": round(float(b[1]), 5),
+                                          "L_norm": round(float(b[3]), 5), "bles_loss": round(float(b[4]), 6)}
+            del bles, bws
+        del xcat, ridx, rgate, rprobs
 
         # ---- the paper's offloading cost model (Sec. 3.4.2) restated on this routing: run the stack
         # token by token, keep every layer's selection, count on the GPU how often a layer's
