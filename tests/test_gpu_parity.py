@@ -82,6 +82,12 @@ def _route_gpu(dev, x_t, w_t, E, k, act, want_probs=True):
     (19, 128, 64, 64, "bf16", True),    # the largest E and k the library takes
     (1500, 1024, 8, 2, "bf16", True),   # many tokens: eight per workgroup, ragged last tile
     (1028, 256, 64, 8, "f32", False),
+    (2048, 2048, 8, 2, "bf16", True),   # phone prefill
+    # 8192 tokens and more with at most 16 experts: the kernel that stages the router in LDS
+    (8200, 2048, 8, 2, "bf16", True),   # phone width, three tokens per wave, ragged token count
+    (8192, 264, 5, 1, "f32", False),    # d not a multiple of the wave stride
+    (8192, 2048, 16, 4, "bf16", False), # the largest router that fits (128 KB)
+    (20000, 512, 8, 8, "bf16", True),   # five tokens per wave, k = E
 ])
 def test_route_matches_oracle(dev, oracle, T, d, E, k, dtype, bias):
     cfg = _cfg(d=d, E=E, k=k, dtype=dtype, seed=300 + T)
@@ -96,10 +102,28 @@ def test_route_matches_oracle(dev, oracle, T, d, E, k, dtype, bias):
         assert np.all(gate == 1.0)
 
 
-def test_route_tie_break_is_lowest_index_bit_exact(dev, oracle):
+def test_route_large_batch_kernel_is_bit_identical_to_the_small_batch_one(dev):
+    # the same tokens routed as one batch of 9000 (router staged in LDS, wave per token) and in
+    # slices of 3000 (wave per expert): logits are summed in the same order, so every output
+    # matches bit for bit
+    cfg = _cfg(d=1024, E=8, k=2, dtype="bf16", seed=321)
+    w_np = wl.make_layer_weights(cfg, with_bias=False)
+    w_np["router_b"] = wl.normal_tensor(cfg.seed, 99, (8,), 0.5, "f32")
+    x_np = wl.make_inputs(cfg, 9000)
+    w_t = weights_to_device({"router_w": w_np["router_w"], "router_b": w_np["router_b"]}, dev)
+    idx, gate, probs = _route_gpu(dev, to_device(x_np, dev), w_t, 8, 2, pkg.MOE_BF16)
+    for lo in range(0, 9000, 3000):
+        i2, g2, p2 = _route_gpu(dev, to_device(np.ascontiguousarray(x_np[lo:lo + 3000]), dev), w_t, 8, 2,
+                                pkg.MOE_BF16)
+        assert np.array_equal(idx[lo:lo + 3000], i2)
+        assert np.array_equal(gate[lo:lo + 3000], g2) and np.array_equal(probs[lo:lo + 3000], p2)
+
+
+@pytest.mark.parametrize("T", [512, 8704])
+def test_route_tie_break_is_lowest_index_bit_exact(dev, oracle, T):
     # entries in {-1, -.5, 0, .5, 1} and a 0/1 router: every partial sum is exact in fp32
     rng = np.random.default_rng(5)
-    E, d, T, k = 8, 64, 512, 3
+    E, d, k = 8, 64, 3
     x = (rng.integers(-2, 3, size=(T, d)) * 0.5).astype(np.float32)
     rw = np.zeros((E, d), np.float32)
     for e in range(E):
