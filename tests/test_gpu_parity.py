@@ -372,6 +372,32 @@ def test_forward_small_shapes_all_expert_kinds(dev, oracle):
                 _forward_case(dev, oracle, cfg, T, residual=(T == 7))
 
 
+def _sweep_cases(n, seed):
+    """n seeded (d, F, E, k, r, base, dtype, T) combinations: widths any multiple of 8, from
+    narrower than one k-step of the GEMM to a few tiles wide; token counts from one to a few
+    hundred; every expert kind."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        d = 8 * int(rng.integers(1, 41))
+        F = 8 * int(rng.integers(1, 65))
+        E = int(rng.integers(1, 13))
+        k = int(rng.integers(1, E + 1))
+        kind = int(rng.integers(0, 3))  # dense / pure L R / shared base + L R
+        r = 0 if kind == 0 else 8 * int(rng.integers(1, 9))
+        dtype = "f32" if rng.integers(0, 4) == 0 else "bf16"
+        T = int(rng.choice([1, 2, 3, 5, 17, 64, 129, 300, 400]))
+        cases.append((d, F, E, k, r, kind == 2, dtype, T))
+    return cases
+
+
+@pytest.mark.parametrize("d,F,E,k,r,base,dtype,T", _sweep_cases(28, 20250300245))
+def test_forward_seeded_shape_sweep(dev, oracle, d, F, E, k, r, base, dtype, T):
+    cfg = _cfg(name="sw", d=d, F=F, E=E, k=k, dtype=dtype, seed=7000 + d + F + E + k + r + T, r=r,
+               base=base, std=0.08)
+    _forward_case(dev, oracle, cfg, T, residual=bool((d + T) % 2))
+
+
 @pytest.mark.parametrize("k,E,T", [(2, 8, 2), (2, 8, 37), (2, 8, 600), (3, 5, 150), (8, 8, 64), (2, 16, 9)])
 def test_forward_shared_base_once_per_token(dev, oracle, k, E, T):
     # bf16 layers with k > 1 take the path that applies the shared base once per token (plain
