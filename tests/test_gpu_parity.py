@@ -398,6 +398,30 @@ def test_forward_seeded_shape_sweep(dev, oracle, d, F, E, k, r, base, dtype, T):
     _forward_case(dev, oracle, cfg, T, residual=bool((d + T) % 2))
 
 
+def _prefill_sweep_cases(n, seed):
+    """n seeded prefill-sized combinations: a few hundred rows per expert and widths up to a dozen
+    tiles, so the 256- and 128-row GEMM kernels run with K tails, ragged groups and cut tiles."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        d = 8 * int(rng.integers(16, 160))
+        F = 8 * int(rng.integers(32, 400))
+        E = int(rng.integers(2, 9))
+        k = int(rng.integers(1, min(E, 4) + 1))
+        kind = int(rng.integers(0, 3))
+        r = 0 if kind == 0 else 8 * int(rng.integers(2, 33))
+        T = int(rng.integers(600, 3000))
+        cases.append((d, F, E, k, r, kind == 2, T))
+    return cases
+
+
+@pytest.mark.parametrize("d,F,E,k,r,base,T", _prefill_sweep_cases(10, 2503))
+def test_forward_seeded_prefill_sweep(dev, oracle, d, F, E, k, r, base, T):
+    cfg = _cfg(name="pf", d=d, F=F, E=E, k=k, dtype="bf16", seed=8000 + d + F + E + k + r + T, r=r,
+               base=base, std=0.04)
+    _forward_case(dev, oracle, cfg, T, sample=16)
+
+
 @pytest.mark.parametrize("k,E,T", [(2, 8, 2), (2, 8, 37), (2, 8, 600), (3, 5, 150), (8, 8, 64), (2, 16, 9)])
 def test_forward_shared_base_once_per_token(dev, oracle, k, E, T):
     # bf16 layers with k > 1 take the path that applies the shared base once per token (plain
