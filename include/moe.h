@@ -24,8 +24,9 @@
  *     kernel is launched (bad argument, unsupported shape, short workspace) or
  *     MOE_ERR_LAUNCH if the runtime refused a launch.  There is no device-side
  *     error reporting; non-finite inputs give unspecified outputs.
- *   - No global state; calls on distinct streams with distinct workspaces and
- *     outputs may run concurrently.  Results are deterministic (no floating
+ *   - No global state (beyond raising, once per device, the LDS limit of the
+ *     kernels that need it); calls on distinct streams with distinct workspaces
+ *     and outputs may run concurrently, from any host thread.  Results are deterministic (no floating
  *     point atomics): the same call on the same inputs returns the same bits.
  *   - Limits: 1 <= k <= E <= 64; d_model, d_ff, rank multiples of 8;
  *     n_tokens * k < 2^24 (n_tokens = 0 is a valid no-op).

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "moe.h"
 
 namespace moe {
@@ -81,6 +83,20 @@ __device__ __forceinline__ float silu_f32(float z) {
 inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
 inline int launch_status() { return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_LAUNCH; }
+
+// Kernels that use more than the default 64 KB of dynamic LDS need the limit raised once per
+// device.  `done` is a per-kernel bit mask of the devices already set up (the only state the
+// library keeps; a race merely repeats the call).
+inline int allow_dynamic_lds(const void* kernel, size_t bytes, std::atomic<uint64_t>& done) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return MOE_ERR_LAUNCH;
+    const uint64_t bit = 1ull << (dev & 63);
+    if (done.load(std::memory_order_acquire) & bit) return MOE_OK;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess)
+        return MOE_ERR_LAUNCH;
+    done.fetch_or(bit, std::memory_order_release);
+    return MOE_OK;
+}
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 

@@ -722,14 +722,11 @@ static int launch_bf16_deep(GemmArgs& g, hipStream_t st) {
         if (K < 8 || K % 8 != 0 || (KG > 1 && K % (BK * KG) != 0)) return MOE_ERR_UNSUPPORTED;
         tail |= K % BK != 0;
     }
-    static bool attr_set[2] = {false, false};
+    static std::atomic<uint64_t> lds_allowed[2];
     auto launch = [&](auto kern, int which) {
-        if (lds > 32 * 1024 && !attr_set[which]) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-                return (int)MOE_ERR_LAUNCH;
-            attr_set[which] = true;
-        }
+        if (lds > 32 * 1024 &&
+            allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds, lds_allowed[which]) != MOE_OK)
+            return (int)MOE_ERR_LAUNCH;
         hipLaunchKernelGGL(kern, dim3(grid), dim3(NTHR), lds, st, g);
         return launch_status();
     };

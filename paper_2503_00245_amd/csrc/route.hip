@@ -127,13 +127,9 @@ template <typename T>
 static int launch_route_lds(const moe_shape& s, const T* x, const float* rw, const float* rb,
                             int32_t* topk_idx, float* topk_gate, float* probs, hipStream_t st) {
     const size_t lds = (size_t)s.n_experts * s.d_model * sizeof(float);
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(route_lds_kernel<T>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kRouteLdsBytes) != hipSuccess)
-            return MOE_ERR_LAUNCH;
-        attr_set = true;
-    }
+    static std::atomic<uint64_t> lds_allowed;
+    if (allow_dynamic_lds(reinterpret_cast<const void*>(route_lds_kernel<T>), kRouteLdsBytes, lds_allowed) != MOE_OK)
+        return MOE_ERR_LAUNCH;
     // up to two workgroups per CU, every wave with the same number of tokens
     const int waves = 2 * 256 * kRouteWaves;
     const int tokens_per_wave = (s.n_tokens + waves - 1) / waves;
