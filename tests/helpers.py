@@ -48,6 +48,31 @@ def rel_err(y, ref):
     return float(max(np.abs(y - ref).max() / den_max, np.linalg.norm(y - ref) / den_l2))
 
 
+def row_rel_err(y, ref):
+    """Worst row: max over rows of (L2 error of the row / L2 norm of the reference row).  A wrong
+    value confined to a few rows cannot hide behind the norm of the whole tensor here."""
+    y = np.asarray(y, np.float64)
+    ref = np.asarray(ref, np.float64)
+    if ref.size == 0:
+        return 0.0
+    den = np.maximum(np.linalg.norm(ref, axis=-1), 1e-300)
+    return float((np.linalg.norm(y - ref, axis=-1) / den).max())
+
+
+def elementwise_rel_err(y, ref, floor=0.1):
+    """Worst element-wise relative error over the elements whose reference magnitude exceeds
+    `floor` times the tensor's rms (element-wise relative error means nothing near zero)."""
+    y = np.asarray(y, np.float64)
+    ref = np.asarray(ref, np.float64)
+    if ref.size == 0:
+        return 0.0
+    rms = np.sqrt(np.mean(ref * ref))
+    big = np.abs(ref) > floor * rms
+    if not big.any():
+        return 0.0
+    return float((np.abs(y - ref)[big] / np.abs(ref)[big]).max())
+
+
 def ambiguous_tokens(logits, x, router_w, k):
     """Tokens whose k-th and (k+1)-th largest fp64 logits are closer than the fp32 rounding
     bound of a length-d dot product: delta = 8 d 2^-24 max|x_t| max|W_r| (any summation order).
