@@ -30,6 +30,14 @@
  *   oracle_expert_replacements  Sec. 2.3 Eq. 4 (H_e, H) and the floor(H/2) of Eq. 5.
  *   oracle_bles_loss    Sec. 2.3 Eq. 4-7, the forward value of the block-wise expert selection loss.
  *   oracle_offload_counters  Sec. 3.4.2: set changes and expert loads under the offloading rule.
+ *   oracle_delta_uniform  Sec. 3.2 (metric list) / Table 3 / Fig. 6: "Delta Uniform", the average
+ *                       over layers of each layer's divergence of the realised expert balance
+ *                       from the uniform one.  The paper prints no formula for a layer's
+ *                       divergence: the reading used here is stated at the function.  What the
+ *                       paper does fix - that the reported figure is the plain mean of the
+ *                       per-layer values - is pinned on Fig. 6 against Table 3; the per-layer
+ *                       formula is PARITY UNPINNED against the paper's numbers (they need the
+ *                       trained routers and the evaluation text).
  *
  * Parity pins (tests/test_oracle_*.py): closed forms, library routines on
  * special cases, brute force on tiny inputs and the worked example of Fig. 5.
@@ -169,9 +177,15 @@ int oracle_route(int T, int d, int E, int k, int dtype, const void* x, const flo
                  const float* rb, int32_t* topk_idx, double* topk_gate, double* probs_out,
                  double* logits_out) {
     if (T < 0 || d < 1 || E < 1 || k < 1 || k > E) return -1;
+    int failed = 0; /* a scratch allocation failed in some iteration */
 #pragma omp parallel for schedule(static) if (T >= 8)
     for (int t = 0; t < T; ++t) {
         double* xv = (double*)malloc(sizeof(double) * ((size_t)d + 2 * (size_t)E));
+        if (!xv) {
+#pragma omp atomic write
+            failed = 1;
+            continue;
+        }
         double* lg = xv + d;
         double* pr = lg + E;
         widen(x, (size_t)t * d, (size_t)d, dtype, xv);
@@ -181,7 +195,7 @@ int oracle_route(int T, int d, int E, int k, int dtype, const void* x, const flo
         if (logits_out) memcpy(logits_out + (size_t)t * E, lg, sizeof(double) * E);
         free(xv);
     }
-    return 0;
+    return failed ? -2 : 0;
 }
 
 /* Stable counting sort of pairs p = 0..P-1 by key topk_idx[p] in [0,E). */
@@ -195,6 +209,7 @@ int oracle_permute(int P, int E, const int32_t* topk_idx, int32_t* expert_offset
     }
     for (int e = 0; e < E; ++e) expert_offsets[e + 1] += expert_offsets[e];
     int32_t* next = (int32_t*)malloc(sizeof(int32_t) * (size_t)E);
+    if (!next) return -2;
     for (int e = 0; e < E; ++e) next[e] = expert_offsets[e];
     for (int p = 0; p < P; ++p) {
         int32_t s = next[topk_idx[p]]++;
@@ -210,18 +225,25 @@ int oracle_expert_ffn(const oracle_layer* L, int P, const void* x_perm,
                       const int32_t* expert_offsets, double* y_perm) {
     if (expert_offsets[0] != 0 || expert_offsets[L->E] != P) return -1;
     int32_t* row_expert = (int32_t*)malloc(sizeof(int32_t) * (size_t)(P > 0 ? P : 1));
+    if (!row_expert) return -2;
+    int failed = 0;
     for (int e = 0; e < L->E; ++e)
         for (int s = expert_offsets[e]; s < expert_offsets[e + 1]; ++s) row_expert[s] = e;
 #pragma omp parallel for schedule(dynamic, 1) if (P >= 8)
     for (int s = 0; s < P; ++s) {
         size_t ns = (size_t)L->d + 2 * (size_t)L->F + (size_t)L->r;
         double* v = (double*)malloc(sizeof(double) * ns);
+        if (!v) {
+#pragma omp atomic write
+            failed = 1;
+            continue;
+        }
         widen(x_perm, (size_t)s * L->d, (size_t)L->d, L->dtype, v);
         expert_ffn_vec(L, row_expert[s], v, y_perm + (size_t)s * L->d, v + L->d);
         free(v);
     }
     free(row_expert);
-    return 0;
+    return failed ? -2 : 0;
 }
 
 /* y[t,:] = sum_j gate[t,j] y_perm[inv_perm[t k + j],:] (+ residual[t,:]), j ascending */
@@ -246,11 +268,19 @@ static int layer_forward_f64(const oracle_layer* L, int T, const double* xin, do
                              int32_t* idx_out, double* gate_out) {
     if (T < 0 || L->k < 1 || L->k > L->E) return -1;
     const int d = L->d, k = L->k, E = L->E;
+    int failed = 0;
 #pragma omp parallel for schedule(dynamic, 1) if (T >= 8)
     for (int t = 0; t < T; ++t) {
         size_t ns = 2 * (size_t)E + (size_t)k + (size_t)d + 2 * (size_t)L->F + (size_t)L->r;
         double* buf = (double*)malloc(sizeof(double) * ns);
         int32_t* idx = (int32_t*)malloc(sizeof(int32_t) * (size_t)k);
+        if (!buf || !idx) {
+            free(buf);
+            free(idx);
+#pragma omp atomic write
+            failed = 1;
+            continue;
+        }
         double* lg = buf;
         double* pr = lg + E;
         double* gate = pr + E;
@@ -271,13 +301,14 @@ static int layer_forward_f64(const oracle_layer* L, int T, const double* xin, do
         free(idx);
         free(buf);
     }
-    return 0;
+    return failed ? -2 : 0;
 }
 
 int oracle_forward(const oracle_layer* L, int T, const void* x, double* y, int32_t* idx_out,
                    double* gate_out) {
     size_t n = (size_t)(T > 0 ? T : 0) * L->d;
     double* xin = (double*)malloc(sizeof(double) * (n ? n : 1));
+    if (!xin) return -2;
     widen(x, 0, n, L->dtype, xin);
     int rc = layer_forward_f64(L, T, xin, y, idx_out, gate_out);
     free(xin);
@@ -296,6 +327,11 @@ int oracle_stack_forward(const oracle_layer* layers, int n_layers, int T, const 
     size_t n = (size_t)(T > 0 ? T : 0) * d;
     double* cur = (double*)malloc(sizeof(double) * (n ? n : 1));
     double* nxt = (double*)malloc(sizeof(double) * (n ? n : 1));
+    if (!cur || !nxt) {
+        free(cur);
+        free(nxt);
+        return -2;
+    }
     widen(x, 0, n, layers[0].dtype, cur);
     int rc = 0;
     for (int l = 0; l < n_layers && rc == 0; ++l) {
@@ -408,5 +444,49 @@ int oracle_offload_counters(int L, int T, int K, int E, const int32_t* trace, in
         changes[l] = ch;
         loads[l] = ld;
     }
+    return 0;
+}
+
+/*
+ * "Delta Uniform" of a routing trace [L,T,K] (Sec. 3.2: the average per-layer delta between the
+ * uniform distribution and the realised expert balance; Table 3 column; Fig. 6 per layer group).
+ * Reading (the paper gives no formula):
+ *   counts[l,e] = #{(t,j) : trace[l,t,j] = e}                     integer
+ *   share[l,e]  = counts[l,e] / (T K)                              realised balance of layer l
+ *   delta[l]    = sum_e | share[l,e] - 1/E |                       L1 distance to the uniform balance
+ *               = mean over experts of |share - 1/E| relative to the uniform share 1/E
+ *   result      = (1/L) sum_l delta[l]                             average per layer
+ * delta is 0 for a perfectly balanced layer and 2 (1 - K/E) when all tokens use the same K experts
+ * (expert collapse: the layer acts as a dense one).  Values are fractions; the paper prints percent.
+ * counts_out [L,E] int64 and delta_out [L] are optional.  Entries outside [0,E) are an error.
+ */
+int oracle_delta_uniform(int L, int T, int K, int E, const int32_t* trace, int64_t* counts_out,
+                         double* delta_out, double* mean_out) {
+    if (L < 1 || T < 1 || K < 1 || E < 1) return -1;
+    int64_t* cnt = (int64_t*)malloc(sizeof(int64_t) * (size_t)E);
+    if (!cnt) return -2;
+    double total = 0.0;
+    for (int l = 0; l < L; ++l) {
+        for (int e = 0; e < E; ++e) cnt[e] = 0;
+        for (int t = 0; t < T; ++t)
+            for (int j = 0; j < K; ++j) {
+                int32_t e = trace[((size_t)l * T + t) * K + j];
+                if (e < 0 || e >= E) {
+                    free(cnt);
+                    return -1;
+                }
+                cnt[e] += 1;
+            }
+        double delta = 0.0;
+        for (int e = 0; e < E; ++e) {
+            double dev = (double)cnt[e] / ((double)T * (double)K) - 1.0 / (double)E;
+            delta += dev < 0 ? -dev : dev;
+            if (counts_out) counts_out[(size_t)l * E + e] = cnt[e];
+        }
+        if (delta_out) delta_out[l] = delta;
+        total += delta;
+    }
+    free(cnt);
+    *mean_out = total / (double)L;
     return 0;
 }

@@ -218,3 +218,17 @@ def offload_counters(trace, n_experts: int):
     if rc != 0:
         raise ValueError(f"oracle_offload_counters rejected its arguments (rc={rc})")
     return ch, ld
+
+
+def delta_uniform(trace, n_experts: int):
+    """Sec. 3.2 / Table 3 "Delta Uniform" of a routing trace int32 [L,T,K] ->
+    (mean over layers, per-layer delta f64 [L], counts int64 [L,E]); fractions, not percent."""
+    tr = _c(trace, np.int32)
+    L, T, K = tr.shape
+    counts = np.zeros((L, n_experts), np.int64)
+    delta = np.zeros(L, np.float64)
+    mean = np.zeros(1, np.float64)
+    rc = lib().oracle_delta_uniform(L, T, K, n_experts, _p(tr), _p(counts), _p(delta), _p(mean))
+    if rc != 0:
+        raise ValueError(f"oracle_delta_uniform rejected its arguments (rc={rc})")
+    return float(mean[0]), delta, counts

@@ -514,3 +514,83 @@ def test_offload_counters_closed_forms_and_order_independence(oracle):
                 n += len(cur - prev)
                 prev = cur
         assert (ch[l], ld[l]) == (c, n)
+
+
+# ----------------------------------------------------------------- Delta Uniform (Sec. 3.2, Table 3, Fig. 6)
+
+def test_delta_uniform_is_the_plain_mean_over_layers_in_the_paper():
+    # what the paper fixes: the Table 3 figure is the mean of the per-layer(-group) values of
+    # Fig. 6 (equal groups of three layers, so the mean of the groups is the mean of the layers)
+    rows = np.loadtxt(os.path.join(GOLDEN, "fig6_delta_uniform.txt"), comments="#")
+    for row in rows:
+        assert round(float(np.mean(row[:8])), 2) == row[8]
+
+
+def test_delta_uniform_closed_forms(oracle):
+    # perfectly balanced layers: every expert holds T K / E pairs -> exactly 0
+    E, K = 8, 2
+    bal = np.stack([np.array([(2 * t) % E, (2 * t + 1) % E]) for t in range(64)]).astype(np.int32)[None]
+    mean, delta, counts = oracle.delta_uniform(bal, E)
+    assert mean == 0.0 and delta[0] == 0.0 and np.all(counts == 16)
+    # expert collapse: all tokens on the same K experts -> 2 (1 - K/E); the value the figure's
+    # caption calls a pseudo-dense layer
+    col = np.tile(np.array([[5, 2]], np.int32), (1, 40, 1))
+    mean, delta, counts = oracle.delta_uniform(col, E)
+    assert mean == 2 * (1 - K / E) and counts[0, 5] == 40 and counts[0, 2] == 40 and counts.sum() == 80
+    # hand-worked: E = 3, K = 1, four tokens on experts 0 0 1 2 -> shares 1/2 1/4 1/4,
+    # |1/2 - 1/3| + 2 |1/4 - 1/3| = 1/3
+    mean, delta, _ = oracle.delta_uniform(np.array([[[0], [0], [1], [2]]], np.int32), 3)
+    assert abs(mean - 1 / 3) < 1e-15
+
+
+def test_delta_uniform_averages_per_layer_values_not_pooled_counts(oracle):
+    # layer 0 uses experts {0,1} only, layer 1 experts {2,3} only (E = 4, K = 2): each layer is
+    # fully collapsed (delta 1), while the counts pooled over both layers are perfectly uniform
+    tr = np.stack([np.tile(np.array([[0, 1]], np.int32), (10, 1)),
+                   np.tile(np.array([[2, 3]], np.int32), (10, 1))])
+    mean, delta, _ = oracle.delta_uniform(tr, 4)
+    assert list(delta) == [1.0, 1.0] and mean == 1.0
+    # unequal layers: the result is their plain mean
+    tr2 = np.stack([np.tile(np.array([[0, 1]], np.int32), (10, 1)),
+                    np.array([[0, 1], [2, 3]] * 5, np.int32)])
+    mean, delta, _ = oracle.delta_uniform(tr2, 4)
+    assert list(delta) == [1.0, 0.0] and mean == 0.5
+
+
+def test_delta_uniform_invariances_and_library_histogram(oracle):
+    rng = np.random.default_rng(17)
+    L, T, K, E = 5, 300, 2, 8
+    scores = rng.standard_normal((L, T, E)) + np.linspace(1, -1, E)
+    tr = np.argsort(-scores, axis=-1)[..., :K].astype(np.int32)
+    mean, delta, counts = oracle.delta_uniform(tr, E)
+    # against a library histogram
+    for l in range(L):
+        c = np.bincount(tr[l].ravel(), minlength=E)
+        assert np.array_equal(counts[l], c)
+        assert np.isclose(delta[l], np.abs(c / (T * K) - 1 / E).sum(), rtol=1e-13, atol=0)
+    assert np.isclose(mean, delta.mean(), rtol=1e-15)
+    assert 0 < mean < 2 * (1 - K / E)
+    # relabelling the experts, reordering the tokens and swapping the slots change nothing
+    relabel = rng.permutation(E).astype(np.int32)
+    m2, d2, c2 = oracle.delta_uniform(relabel[tr], E)
+    assert np.allclose(d2, delta, rtol=1e-14) and np.array_equal(np.sort(c2, 1), np.sort(counts, 1))
+    m3, d3, c3 = oracle.delta_uniform(np.ascontiguousarray(tr[:, ::-1, ::-1]), E)
+    assert np.array_equal(c3, counts) and np.array_equal(d3, delta) and m3 == mean
+    with pytest.raises(ValueError):
+        oracle.delta_uniform(np.full((1, 2, 1), E, np.int32), E)
+
+
+def test_expert_replacements_with_a_repeated_expert_make_H_odd_and_eq5_floors(oracle):
+    # a token that lists one expert twice holds one expert; going to a two-expert token adds ONE
+    # to H (Eq. 4), and Eq. 5 floors H / 2: H_norm is 0, not 0.5 / (B K (T - 1))
+    S = np.array([[[0, 0], [0, 1]]], np.int32)
+    H, He = oracle.expert_replacements(S, 4)
+    assert H == 1 and list(He) == [0, 1, 0, 0]
+    W = np.array([[[0.5, 0.5, 0, 0], [0.25, 0.75, 0, 0]]], np.float32)
+    r = oracle.bles_loss(W, S)
+    assert r["H"] == 1 and r["H_norm"] == 0.0 and r["L"] == 0.5 and r["loss"] == 0.0
+    # three tokens: H = 1 + 2 = 3, floor(3 / 2) = 1 -> H_norm = 1 / (1 * 2 * 2)
+    S3 = np.array([[[0, 0], [0, 1], [2, 1]]], np.int32)
+    W3 = np.concatenate([W, W[:, :1]], axis=1)
+    r = oracle.bles_loss(W3, S3)
+    assert r["H"] == 3 and r["H_norm"] == 0.25
