@@ -573,8 +573,14 @@ def test_stack_phone_full_depth_decode_loop(dev, oracle):
             if same[0]:
                 ref, _, _ = oracle.forward(layers_np[l], xin, k, residual=True)
                 e = rel_err(to_f64(yl), ref)
-                forced_worst = max(forced_worst, e)
                 assert e < TOL["bf16"], f"step {step} layer {l}: teacher-forced error {e:.3e}"
+                # the stream is mostly the residual, so also compare the layer's own contribution
+                yc, idx_c, _ = _forward_gpu(dev, layers_t[l], to_device(xin, dev), k, pkg.MOE_BF16)
+                assert np.array_equal(idx_c, idx)
+                ref_c, _, _ = oracle.forward(layers_np[l], xin, k)
+                ec = rel_err(to_f64(yc), ref_c)
+                assert ec < TOL["bf16"], f"step {step} layer {l}: error of the layer's contribution {ec:.3e}"
+                forced_worst = max(forced_worst, e, ec)
     print(f"[stack24] {clean_steps}/{n_steps} steps without a routing flip, worst free-running error on them "
           f"{max(free_errs) if free_errs else float('nan'):.3e}; worst teacher-forced layer error {forced_worst:.3e}; "
           f"teacher-forced ambiguous picks {n_amb}")

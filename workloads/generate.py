@@ -45,6 +45,7 @@ class LayerConfig:
     weight_std: float = 0.02
     router_std: float = 0.02
     wd_product_std: float = 0.02  # target std of the entries of L.R
+    down_std: Optional[float] = None  # std of the dense down projection; None: weight_std
 
 
 CONFIGS: Dict[str, LayerConfig] = {
@@ -59,8 +60,13 @@ CONFIGS: Dict[str, LayerConfig] = {
     # phone-shaped, shared dense base plus a rank-64 expert-specific pair
     "phone_wd_base": LayerConfig("phone_wd_base", 2048, 5632, 8, 2, "bf16", 245014,
                                  rank=64, shared_base=True, wd_product_std=0.005),
-    # 24 phone-shaped layers run back to back with residual adds
-    "phone_stack": LayerConfig("phone_stack", 2048, 5632, 8, 2, "bf16", 245005, n_layers=24),
+    # 24 phone-shaped layers run back to back with residual adds.  The stack has no normalisation,
+    # and a SwiGLU block is quadratic in the size of its input, so with every matrix at N(0, 0.02)
+    # the residual stream squares its size every layer once it exceeds about 2 and overflows
+    # (fp64 included) by the 13th layer.  The down projections are therefore drawn with the usual
+    # residual-branch scaling 0.02 / sqrt(2 n_layers), which keeps the stream's rms near 1.
+    "phone_stack": LayerConfig("phone_stack", 2048, 5632, 8, 2, "bf16", 245005, n_layers=24,
+                               down_std=0.02 / (2 * 24) ** 0.5),
     # The paper's own model rows (Table 1: hidden size per row; d_ff taken as 8/3 of it, rounded to
     # a multiple of 8; 8 experts, 2 active as in Sec. 3.1).  Widths that are not multiples of 64.
     "paper_phone": LayerConfig("paper_phone", 1440, 3840, 8, 2, "bf16", 245021),
@@ -158,7 +164,8 @@ def make_layer_weights(cfg: LayerConfig, layer: int = 0,
         eb = 1 if cfg.shared_base else E
         w["w_gate"] = normal_tensor(seed, _TID["w_gate"], (eb, F, d), cfg.weight_std, dt)
         w["w_up"] = normal_tensor(seed, _TID["w_up"], (eb, F, d), cfg.weight_std, dt)
-        w["w_down"] = normal_tensor(seed, _TID["w_down"], (eb, d, F), cfg.weight_std, dt)
+        w["w_down"] = normal_tensor(seed, _TID["w_down"], (eb, d, F),
+                                    cfg.weight_std if cfg.down_std is None else cfg.down_std, dt)
     if r > 0:
         sigma = float(np.sqrt(cfg.wd_product_std / np.sqrt(r)))
         w["rg"] = normal_tensor(seed, _TID["rg"], (E, r, d), sigma, dt)
