@@ -163,6 +163,23 @@ MOE_API int moe_forward(const moe_shape* shape, const moe_weights* weights, cons
                 void* stream);
 
 /*
+ * moe_forward for callers that cannot allocate or pass a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the same
+ * results as moe_forward, bit for bit; the scratch is an array inside the library, held by every
+ * GPU the library runs on until the process ends (its device address is looked up on the first
+ * call on a device).  The call allocates and frees nothing.
+ *   - shapes whose moe_workspace_bytes() exceeds MOE_STATIC_WORKSPACE_BYTES are refused with
+ *     MOE_ERR_WORKSPACE before any launch (single-token steps of every size fit; a 2048 / 5632
+ *     layer up to about 230 tokens);
+ *   - every call on one GPU uses that GPU's one array: calls that overlap in time on the same GPU
+ *     (two streams, two threads) race; calls on one stream, or otherwise ordered, are fine.
+ *     Nothing in the array has to be cleared between calls.
+ */
+#define MOE_STATIC_WORKSPACE_BYTES (8u << 20)
+MOE_API int moe_forward_static(const moe_shape* shape, const moe_weights* weights, const void* x,
+                               void* y, int32_t* topk_idx, float* topk_gate, void* stream);
+
+/*
  * Residual stack of n_layers layers of one shape: x_{l+1} = x_l + layer_l(x_l), no
  * normalisation, activations between layers stored in act_dtype.  `layers` is a
  * host array of n_layers weight structs.  y [T, d] receives x_{n_layers}.

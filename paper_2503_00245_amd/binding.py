@@ -20,7 +20,7 @@ FLAG_SHARED_BASE, FLAG_RESIDUAL = 1, 2
 WEIGHT_FIELDS = ("router_w", "router_b", "w_gate", "w_up", "w_down",
                  "rg", "ru", "rd", "lg", "lu", "ld")
 EXPORTS = ("moe_route", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_forward",
-           "moe_stack_forward", "moe_forward_timed", "moe_workspace_bytes", "moe_status_string",
+           "moe_forward_static", "moe_stack_forward", "moe_forward_timed", "moe_workspace_bytes", "moe_status_string",
            "moe_expert_replacements", "moe_bles_workspace_bytes", "moe_bles_loss",
            "moe_offload_counters")
 
@@ -63,6 +63,7 @@ def lib() -> C.CDLL:
         L.moe_expert_ffn.argtypes = [sp, wp, vp, vp, vp, vp, sz, vp]
         L.moe_combine.argtypes = [sp, vp, vp, vp, vp, vp, vp]
         L.moe_forward.argtypes = [sp, wp, vp, vp, vp, vp, vp, sz, vp]
+        L.moe_forward_static.argtypes = [sp, wp, vp, vp, vp, vp, vp]
         L.moe_stack_forward.argtypes = [sp, wp, C.c_int32, vp, vp, vp, vp, sz, vp]
         L.moe_forward_timed.argtypes = [sp, wp, vp, vp, vp, sz, vp, C.POINTER(C.c_float),
                                         C.POINTER(C.c_char_p), C.POINTER(C.c_int32)]
@@ -73,7 +74,7 @@ def lib() -> C.CDLL:
         L.moe_bles_loss.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, sz, vp]
         L.moe_offload_counters.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp]
         for fn in ("moe_route", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_forward",
-                   "moe_stack_forward", "moe_forward_timed", "moe_expert_replacements",
+                   "moe_forward_static", "moe_stack_forward", "moe_forward_timed", "moe_expert_replacements",
                    "moe_bles_loss", "moe_offload_counters"):
             getattr(L, fn).restype = C.c_int
         _lib = L
@@ -179,6 +180,16 @@ def moe_forward(shape: MoeShape, weights: MoeWeights, x, y, topk_idx=None, topk_
     _check("moe_forward", lib().moe_forward(
         C.byref(shape), C.byref(weights), _ptr(x), _ptr(y), _ptr(topk_idx), _ptr(topk_gate),
         _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream(y.device)))
+
+
+STATIC_WORKSPACE_BYTES = 8 << 20
+
+
+def moe_forward_static(shape: MoeShape, weights: MoeWeights, x, y, topk_idx=None, topk_gate=None) -> None:
+    """moe_forward on the library's own scratch array: no workspace argument, no allocation."""
+    _check("moe_forward_static", lib().moe_forward_static(
+        C.byref(shape), C.byref(weights), _ptr(x), _ptr(y), _ptr(topk_idx), _ptr(topk_gate),
+        _stream(y.device)))
 
 
 def moe_stack_forward(shape: MoeShape, layers: Sequence[MoeWeights], x, y, topk_trace=None,

@@ -102,6 +102,28 @@ static int forward_impl(const moe_shape& s, const moe_weights& w, const void* x,
     return rc;
 }
 
+// ---- scratch of the allocation-free entry point ------------------------------------------------
+// A file-scope device array stands in for the caller's workspace.  Every GPU the library runs on
+// holds its own copy at its own address until the process ends; in host code the array's name is
+// only a handle for the runtime, so the device address is looked up once per device (with that
+// device current) and kept, and only that pointer is ever handed to kernels.
+static __device__ __align__(256) unsigned char scratch[MOE_STATIC_WORKSPACE_BYTES];
+constexpr int kMaxDevices = 64;
+static std::atomic<void*> scratch_ptr[kMaxDevices];
+
+static int static_scratch(char** out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return MOE_ERR_LAUNCH;
+    if (dev < 0 || dev >= kMaxDevices) return MOE_ERR_UNSUPPORTED;
+    void* p = scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {  // first call on this device (a race merely repeats the lookup)
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return MOE_ERR_LAUNCH;
+        scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *out = static_cast<char*>(p);
+    return MOE_OK;
+}
+
 }  // namespace moe
 
 using namespace moe;
@@ -190,6 +212,20 @@ int moe_forward(const moe_shape* shape, const moe_weights* weights, const void* 
         return MOE_ERR_WORKSPACE;
     return forward_impl(*shape, *weights, x, y, topk_idx, topk_gate, static_cast<char*>(workspace),
                         as_stream(stream));
+}
+
+int moe_forward_static(const moe_shape* shape, const moe_weights* weights, const void* x, void* y,
+                       int32_t* topk_idx, float* topk_gate, void* stream) {
+    int rc = validate_shape(shape);
+    if (rc != MOE_OK) return rc;
+    if ((rc = validate_weights(*shape, weights, true)) != MOE_OK) return rc;
+    if (shape->n_tokens == 0) return MOE_OK;
+    if (!x || !y || x == y || !aligned16(x) || !aligned16(y)) return MOE_ERR_INVALID;
+    if (carve(*shape).total > (size_t)MOE_STATIC_WORKSPACE_BYTES) return MOE_ERR_WORKSPACE;
+    char* wsp = nullptr;
+    if ((rc = static_scratch(&wsp)) != MOE_OK) return rc;
+    // nothing in the workspace has to start at zero: every stage writes what the next one reads
+    return forward_impl(*shape, *weights, x, y, topk_idx, topk_gate, wsp, as_stream(stream));
 }
 
 int moe_forward_timed(const moe_shape* shape, const moe_weights* weights, const void* x, void* y,

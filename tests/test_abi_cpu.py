@@ -18,7 +18,7 @@ def _declared():
 
 def test_library_exports_every_declared_symbol():
     names = _declared()
-    assert set(names) == set(pkg.EXPORTS) and len(names) == 13
+    assert set(names) == set(pkg.EXPORTS) and len(names) == 14
     L = pkg.lib()
     for n in names:
         assert getattr(L, n) is not None
@@ -111,3 +111,19 @@ def test_trace_metric_entry_points_reject_bad_shapes_on_the_host():
     assert pkg.moe_bles_workspace_bytes(4, 128, 65) == 0
     assert L.moe_bles_loss(ok, ok, 4, 128, 2, 8, ok, ok, 16, None) == -3       # short workspace
     assert L.moe_bles_loss(ok, ok, 4, 128, 2, 8, None, ok, 1 << 20, None) == -1
+
+
+def test_static_entry_point_refuses_what_its_scratch_cannot_hold():
+    # checked on the host, before the scratch array is even looked up
+    L = pkg.lib()
+    w = pkg.MoeWeights()
+    for n in ("router_w", "w_gate", "w_up", "w_down"):
+        setattr(w, n, 4096)
+    ok, y = C.c_void_p(4096), C.c_void_p(8192)
+    big = pkg.make_shape(2048, 2048, 5632, 8, 2)
+    assert pkg.moe_workspace_bytes(big) > pkg.STATIC_WORKSPACE_BYTES
+    assert L.moe_forward_static(C.byref(big), C.byref(w), ok, y, None, None, None) == -3
+    assert L.moe_forward_static(C.byref(big), C.byref(w), ok, ok, None, None, None) == -1  # y aliases x
+    assert L.moe_forward_static(C.byref(pkg.make_shape(8, 100, 256, 4, 2)), C.byref(w), ok, y, None, None, None) == -2
+    one = pkg.make_shape(1, 2048, 5632, 8, 2)
+    assert 0 < pkg.moe_workspace_bytes(one) <= pkg.STATIC_WORKSPACE_BYTES
