@@ -17,7 +17,13 @@ synchronisation; one JSON line is printed.
   stages     average milliseconds of every stage kernel from that second pass
   latency_ms median / p10 / p90 of single steps (one event pair per step, own pass)
   graph_replay_ms_per_step  the same steps captured once into a HIP graph and replayed
-  gpu_state  shader clock and board power from sysfs right before and after the timed steps
+  preheat    untimed steps of the same workload run before the warm-up until the board has left its
+             idle power state (at least 0.3 s, until two power readings 50 ms apart agree within 3 %,
+             at most 2 s); without it the first milliseconds after idle run at a ramping clock
+  gpu_state  shader clock and board power from sysfs before the pre-heat, after it, while the timed
+             steps are executing (read after they are all enqueued) and after them
+  configs    (default run only) the other benchmark configurations, measured briefly in the same
+             process: ms per step, dominant-kernel and whole-layer roofline fractions
   decode     (default workload only) the same layer at one token per step: ms per step, tokens/s
              and the HBM roofline of its dominant kernel -- the metric's third part
   cpu_baseline  the CPU oracle, as it stands, timed on this host on a bounded sample
@@ -145,6 +151,29 @@ def gpu_state():
     return out or None
 
 
+def preheat(step, sync, min_s=0.3, max_s=2.0):
+    """Run untimed steps until the board power has stopped climbing; returns (seconds, steps)."""
+    t0 = time.perf_counter()
+    n = 0
+    last = None
+    while True:
+        t1 = time.perf_counter()
+        while time.perf_counter() - t1 < 0.05:
+            for _ in range(4):
+                step(n)
+                n += 1
+            sync()
+        el = time.perf_counter() - t0
+        st = gpu_state() or {}
+        pw = st.get("power_w")
+        if el >= max_s:
+            break
+        if el >= min_s and (pw is None or (last is not None and abs(pw - last) <= 0.03 * max(pw, 1.0))):
+            break
+        last = pw
+    return time.perf_counter() - t0, n
+
+
 def percentile(sorted_vals, q):
     return sorted_vals[min(len(sorted_vals) - 1, int(q * len(sorted_vals)))]
 
@@ -161,6 +190,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode-leg", action="store_true",
                     help="default workload only: skip the single-token decode measurement appended as 'decode'")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="default workload only: skip the brief measurements of the other configurations ('configs')")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run three 256 MiB device copies (a known-size kernel that scales the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -186,7 +217,7 @@ def main():
     dev = torch.device("cuda:0")
     weight_cache = {}
 
-    def run_workload(workload, tokens, steps_arg, warmup_arg, want_cpu):
+    def run_workload(workload, tokens, steps_arg, warmup_arg, want_cpu, brief=False):
         cfg_name, T = WORKLOADS[workload]
         if tokens is not None:
             T = tokens
@@ -248,6 +279,8 @@ def main():
             torch.cuda.synchronize()
             del src, dst
 
+        state_idle = gpu_state()
+        preheat_s, preheat_steps = preheat(step, torch.cuda.synchronize)
         state_before = gpu_state()
         for i in range(warmup):
             step(i)
@@ -255,6 +288,7 @@ def main():
         t0 = time.perf_counter()
         for i in range(steps):
             step(warmup + i)
+        state_during = gpu_state() if not brief else None  # the steps are enqueued and executing
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
         ms_per_step = elapsed / steps * 1e3
@@ -276,8 +310,8 @@ def main():
 
         # ---- the same steps replayed from a HIP graph: launch gaps between kernels drop out ------
         graph_ms = None
-        if not stack:
-            n_in_graph = len(w_structs) if decode else 4
+        if not stack and not brief:
+            n_in_graph = 4 * len(w_structs) if decode else 16
             side = torch.cuda.Stream()
             side.wait_stream(torch.cuda.current_stream())
             with torch.cuda.stream(side):
@@ -289,7 +323,7 @@ def main():
                         step(i)
             torch.cuda.current_stream().wait_stream(side)
             torch.cuda.synchronize()
-            n_rep = max(3, min(steps, 200) // n_in_graph)
+            n_rep = max(5, min(steps, 200) // n_in_graph)
             for _ in range(2):
                 graph.replay()
             torch.cuda.synchronize()
@@ -325,15 +359,26 @@ def main():
         else:
             achieved = work / (kms * 1e-3) / 1e12
             peak = MFMA_BF16_PEAK_TFLOPS
-        roofline = {"bound": bound, "achieved": round(achieved, 2), "peak": peak, "unit": unit,
-                    "frac": round(achieved / peak, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(workload) if tokens is None else None,
-                    "kernel": kname, "kernel_ms": round(kms, 5), "algorithmic_per_launch": work}
         flops, wbytes = layer_algorithmic(cfg, T)
         n_l = cfg.n_layers
         layer = {"mfma_frac_of_peak": round(flops * n_l / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
                  "hbm_frac_of_peak": round(wbytes * n_l / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                  "algorithmic_flops": flops * n_l, "algorithmic_weight_bytes": wbytes * n_l,
                  "sum_of_stage_ms": round(sum(stages.values()), 5)}
+        # frac: the dominant kernel alone (its own launches); layer_frac: the whole step against the
+        # same peak, every kernel and every gap between them included
+        roofline = {"bound": bound, "achieved": round(achieved, 2), "peak": peak, "unit": unit,
+                    "frac": round(achieved / peak, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(workload) if tokens is None else None,
+                    "kernel": kname, "kernel_ms": round(kms, 5), "algorithmic_per_launch": work,
+                    "layer_frac": layer["hbm_frac_of_peak"] if bound == "hbm" else layer["mfma_frac_of_peak"]}
+        if brief:
+            return {"tokens_per_step": T, "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 5),
+                    "tokens_per_s": round(tokens_per_s, 2), "roofline": roofline,
+                    "layer_mfma_frac_of_peak": layer["mfma_frac_of_peak"],
+                    "layer_hbm_frac_of_peak": layer["hbm_frac_of_peak"],
+                    "stages_ms": {k: round(v, 5) for k, v in stages.items()},
+                    "latency_ms": latency, "preheat_s": round(preheat_s, 3),
+                    "weight_copies_rotated": len(copies)}
 
         # ---- what the router does with the timed inputs: share of the (token, slot) pairs per expert
         # (first layer; for single-token steps over all the rotated input tokens) --------------------
@@ -347,6 +392,11 @@ def main():
         torch.cuda.synchronize()
         counts = np.bincount(ridx.cpu().numpy().ravel(), minlength=cfg.n_experts)
         routing = {"tokens": int(n_routed), "expert_share": [round(float(c) / counts.sum(), 4) for c in counts]}
+        du_c = torch.zeros((1, cfg.n_experts), dtype=torch.int64, device=dev)
+        du_m = torch.zeros(1, dtype=torch.float64, device=dev)
+        pkg.moe_delta_uniform(ridx.view(1, n_routed, cfg.top_k), cfg.n_experts, du_c, None, du_m)
+        torch.cuda.synchronize()
+        routing["delta_uniform_percent"] = round(100.0 * float(du_m.item()), 3)
         if n_routed > 1:
             # the same tokens read as one sequence: Eq. 4-7's replacement count and loss value
             bles = torch.zeros(5, dtype=torch.float64, device=dev)
@@ -386,8 +436,17 @@ def main():
                        "set_changes_first_and_last_layer": [round(int(changes[0].item()) / n_tr, 4),
                                                             round(int(changes[-1].item()) / n_tr, 4)],
                        "expert_replacements_half_H": int(h_all.item()) // 2,
-                       "note": "independent random tokens: the first layer routes them independently; deeper in "
-                               "this un-normalised residual stack the streams share a growing common part"}
+                       "note": "independent random tokens, so consecutive tokens share experts only by chance"}
+            # Delta Uniform (Sec. 3.2 / Table 3) of the same trace: per-layer L1 distance of the
+            # realised expert shares from 1/E, averaged over the layers
+            du_counts = torch.zeros((cfg.n_layers, cfg.n_experts), dtype=torch.int64, device=dev)
+            du_layer = torch.zeros(cfg.n_layers, dtype=torch.float64, device=dev)
+            du_mean = torch.zeros(1, dtype=torch.float64, device=dev)
+            pkg.moe_delta_uniform(trace, cfg.n_experts, du_counts, du_layer, du_mean)
+            torch.cuda.synchronize()
+            offload["delta_uniform_percent"] = round(100.0 * float(du_mean.item()), 3)
+            offload["delta_uniform_percent_first_and_last_layer"] = [
+                round(100.0 * float(du_layer[0].item()), 3), round(100.0 * float(du_layer[-1].item()), 3)]
             del trace_tl, trace
 
         # ---- CPU oracle baseline on a bounded sample of the same workload -------------------------
@@ -439,7 +498,9 @@ def main():
             "roofline": roofline, "cpu_baseline": cpu, "stages_ms": {k: round(v, 5) for k, v in stages.items()},
             "layer": layer, "routing": routing, "offload_model": offload,
             "latency_ms": latency, "graph_replay_ms_per_step": None if graph_ms is None else round(graph_ms, 5),
-            "gpu_state": {"before": state_before, "after": state_after},
+            "preheat": {"seconds": round(preheat_s, 3), "steps": preheat_steps,
+                        "note": "untimed steps of the same workload before the warm-up, until board power settles"},
+            "gpu_state": {"idle": state_idle, "before": state_before, "during": state_during, "after": state_after},
             "input_generation_s": round(gen_s, 1),
         }
         return out
@@ -455,6 +516,19 @@ def main():
         out["decode"]["workload"] = "phone_decode"
         out["decode"]["layer_hbm_frac_of_peak"] = d["layer"]["hbm_frac_of_peak"]
         out["decode"]["weight_copies_rotated"] = d["config"]["weight_copies_rotated"]
+        out["decode"]["preheat"] = d["preheat"]
+        if not args.no_other_configs:
+            # the other benchmark configurations, briefly, in the same process (each: pre-heat, warm-up,
+            # timed steps, a per-stage event pass); steps chosen so that the whole run stays short
+            others = {}
+            for name, n_steps, n_warm in (("wearables_prefill", 100, 10), ("wearables_decode", 1000, 50),
+                                          ("phone_wd_prefill", 40, 5), ("phone_wd_decode", 500, 20),
+                                          ("phone_wd_base_prefill", 40, 5), ("phone_wd_base_decode", 500, 20),
+                                          ("phone_stack_decode", 48, 4)):
+                weight_cache.clear()
+                torch.cuda.empty_cache()
+                others[name] = run_workload(name, None, n_steps, n_warm, False, brief=True)
+            out["configs"] = others
     print(json.dumps(out))
 
 

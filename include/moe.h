@@ -239,6 +239,23 @@ MOE_API int moe_bles_loss(const float* probs, const int32_t* S, int32_t B, int32
 MOE_API int moe_offload_counters(const int32_t* trace, int32_t L, int32_t T, int32_t K, int32_t E,
                                  int64_t* changes, int64_t* loads, void* stream);
 
+/*
+ * "Delta Uniform" of a routing trace [L,T,K] (Sec. 3.2: the average per-layer delta between the
+ * uniform distribution and the realised expert balance; the third column of Table 3, per group of
+ * layers in Fig. 6).  The paper prints no formula for a layer's delta; this library takes the L1
+ * distance between the layer's realised shares and the uniform share,
+ *   counts[l,e] = #{(t,j) : trace[l,t,j] = e},   share = counts / (T K),
+ *   delta[l] = sum_e | share[l,e] - 1/E |   (= the mean over experts of |share - 1/E| relative to 1/E),
+ *   mean = (1/L) sum_l delta[l],
+ * as fractions (the paper prints percent): 0 for a balanced layer, 2 (1 - K/E) when every token
+ * uses the same K experts.  That the reported figure is the plain mean over layers is the paper's
+ * (Fig. 6's values average to Table 3's); the per-layer formula is this library's reading.
+ * counts [L,E] int64, mean [1] fp64, delta [L] fp64 or NULL: device outputs.  Entries of the trace
+ * outside [0,E) are ignored.
+ */
+MOE_API int moe_delta_uniform(const int32_t* trace, int32_t L, int32_t T, int32_t K, int32_t E,
+                              int64_t* counts, double* delta, double* mean, void* stream);
+
 /* Bytes of workspace that any entry point above needs for this shape (0 if invalid). */
 MOE_API size_t moe_workspace_bytes(const moe_shape* shape);
 

@@ -28,14 +28,23 @@ class _Layer(C.Structure):
 
 
 def lib() -> C.CDLL:
+    """The oracle library.  MOE_ORACLE_LIB names another build of the same source to load instead
+    (the mutation check points it at deliberately broken copies)."""
     global _lib
     if _lib is None:
-        if not os.path.exists(_LIB_PATH):
+        path = os.environ.get("MOE_ORACLE_LIB") or _LIB_PATH
+        if path == _LIB_PATH and not os.path.exists(_LIB_PATH):
             from . import build as _b
             _b.build()
-        _lib = C.CDLL(_LIB_PATH)
-        _lib.oracle_expert_replacements.restype = C.c_int64
+        use_library(path)
     return _lib
+
+
+def use_library(path: str) -> None:
+    """Switch every call below to the build of the oracle at `path`."""
+    global _lib
+    _lib = C.CDLL(path)
+    _lib.oracle_expert_replacements.restype = C.c_int64
 
 
 def num_threads() -> int:

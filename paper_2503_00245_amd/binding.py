@@ -22,7 +22,7 @@ WEIGHT_FIELDS = ("router_w", "router_b", "w_gate", "w_up", "w_down",
 EXPORTS = ("moe_route", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_forward",
            "moe_forward_static", "moe_stack_forward", "moe_forward_timed", "moe_workspace_bytes", "moe_status_string",
            "moe_expert_replacements", "moe_bles_workspace_bytes", "moe_bles_loss",
-           "moe_offload_counters")
+           "moe_offload_counters", "moe_delta_uniform")
 
 
 class MoeShape(C.Structure):
@@ -73,9 +73,10 @@ def lib() -> C.CDLL:
         L.moe_bles_workspace_bytes.restype = C.c_size_t
         L.moe_bles_loss.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, sz, vp]
         L.moe_offload_counters.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp]
+        L.moe_delta_uniform.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp]
         for fn in ("moe_route", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_forward",
                    "moe_forward_static", "moe_stack_forward", "moe_forward_timed", "moe_expert_replacements",
-                   "moe_bles_loss", "moe_offload_counters"):
+                   "moe_bles_loss", "moe_offload_counters", "moe_delta_uniform"):
             getattr(L, fn).restype = C.c_int
         _lib = L
     return _lib
@@ -239,3 +240,10 @@ def moe_offload_counters(trace, n_experts: int, changes, loads) -> None:
     L_, T, K = trace.shape
     _check("moe_offload_counters", lib().moe_offload_counters(
         _ptr(trace), L_, T, K, n_experts, _ptr(changes), _ptr(loads), _stream(trace.device)))
+
+
+def moe_delta_uniform(trace, n_experts: int, counts, delta, mean) -> None:
+    """trace int32 [L,T,K]; counts int64 [L,E], delta f64 [L] (or None), mean f64 [1]: device outputs."""
+    L_, T, K = trace.shape
+    _check("moe_delta_uniform", lib().moe_delta_uniform(
+        _ptr(trace), L_, T, K, n_experts, _ptr(counts), _ptr(delta), _ptr(mean), _stream(trace.device)))

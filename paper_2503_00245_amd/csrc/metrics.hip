@@ -1,7 +1,9 @@
 // Routing-trace statistics the paper defines on the router's outputs:
 //   - hard expert replacements H_e, H (Sec. 2.3, Eq. 4) and floor(H/2) of Eq. 5;
 //   - the forward value of the block-wise expert selection loss (Eq. 4-7);
-//   - set changes and expert loads under the offloading rule of Sec. 3.4.2.
+//   - set changes and expert loads under the offloading rule of Sec. 3.4.2;
+//   - "Delta Uniform" (Sec. 3.2 metric list, Table 3, Fig. 6): per-layer divergence of the
+//     realised expert balance from the uniform one, and its mean over layers.
 // All integer work uses integer atomics (order-independent, hence deterministic); the one
 // floating-point reduction (Eq. 6) sums fixed-size blocks in a fixed tree order and adds the
 // block sums in index order in fp64.
@@ -129,6 +131,41 @@ __global__ __launch_bounds__(kMetricThreads) void offload_kernel(
     }
 }
 
+// counts[l][e] += pairs of layer l that chose expert e (grid: x = token chunks, y = layers)
+__global__ __launch_bounds__(kMetricThreads) void balance_count_kernel(
+    const int32_t* __restrict__ trace, int TK, int E, unsigned long long* __restrict__ counts) {
+    __shared__ int s_cnt[kMaxExperts];
+    if (threadIdx.x < kMaxExperts) s_cnt[threadIdx.x] = 0;
+    __syncthreads();
+    const int32_t* tr = trace + (size_t)blockIdx.y * TK;
+    const int stride = gridDim.x * kMetricThreads;
+    for (int i = blockIdx.x * kMetricThreads + threadIdx.x; i < TK; i += stride) {
+        const int e = tr[i];
+        if ((unsigned)e < (unsigned)E) atomicAdd(&s_cnt[e], 1);
+    }
+    __syncthreads();
+    if (threadIdx.x < E && s_cnt[threadIdx.x])
+        atomicAdd(&counts[(size_t)blockIdx.y * E + threadIdx.x], (unsigned long long)s_cnt[threadIdx.x]);
+}
+
+// delta[l] = sum_e | counts[l][e] / (T K) - 1/E |, summed in ascending e; mean = (sum_l delta[l]) / L
+// in ascending l.  One thread: L E terms of fp64.
+__global__ void balance_finalize_kernel(const unsigned long long* __restrict__ counts, int L, int TK,
+                                        int E, double* __restrict__ delta, double* __restrict__ mean) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    double total = 0.0;
+    for (int l = 0; l < L; ++l) {
+        double dl = 0.0;
+        for (int e = 0; e < E; ++e) {
+            const double dev = (double)counts[(size_t)l * E + e] / (double)TK - 1.0 / (double)E;
+            dl += dev < 0 ? -dev : dev;
+        }
+        if (delta) delta[l] = dl;
+        total += dl;
+    }
+    *mean = total / (double)L;
+}
+
 static int launch_replacements(const int32_t* S, int B, int T, int K, int E, unsigned long long* He,
                                unsigned long long* H, hipStream_t st) {
     hipLaunchKernelGGL(zero_u64_kernel, dim3(1), dim3(kMaxExperts), 0, st, He, E);
@@ -204,6 +241,24 @@ int moe_offload_counters(const int32_t* trace, int32_t L, int32_t T, int32_t K, 
     hipLaunchKernelGGL(offload_kernel, dim3(L), dim3(kMetricThreads), 0, as_stream(stream), trace, T,
                        K, E, reinterpret_cast<unsigned long long*>(changes),
                        reinterpret_cast<unsigned long long*>(loads));
+    return launch_status();
+}
+
+int moe_delta_uniform(const int32_t* trace, int32_t L, int32_t T, int32_t K, int32_t E,
+                      int64_t* counts, double* delta, double* mean, void* stream) {
+    int rc = check_trace_shape(L, T, K, E);
+    if (rc != MOE_OK) return rc;
+    if (!trace || !counts || !mean) return MOE_ERR_INVALID;
+    if ((long long)L * E >= (1ll << 31)) return MOE_ERR_UNSUPPORTED;
+    hipStream_t st = as_stream(stream);
+    unsigned long long* cnt = reinterpret_cast<unsigned long long*>(counts);
+    const int n = L * E;
+    hipLaunchKernelGGL(zero_u64_kernel, dim3((n + kMetricThreads - 1) / kMetricThreads), dim3(kMetricThreads), 0,
+                       st, cnt, n);
+    const int TK = T * K;  // < 2^31 by check_trace_shape
+    const int chunks = min(64, (TK + 4 * kMetricThreads - 1) / (4 * kMetricThreads));
+    hipLaunchKernelGGL(balance_count_kernel, dim3(chunks, L), dim3(kMetricThreads), 0, st, trace, TK, E, cnt);
+    hipLaunchKernelGGL(balance_finalize_kernel, dim3(1), dim3(64), 0, st, cnt, L, TK, E, delta, mean);
     return launch_status();
 }
 

@@ -682,6 +682,46 @@ def test_offload_counters_match_oracle_bit_exact(dev, oracle, L, T, K, E):
         assert rld[0] == 2 + 21  # the paper's 21 replacements after the initial fill
 
 
+@pytest.mark.parametrize("case", ["fig5", "random", "single_token", "wide", "long", "collapsed", "stray"])
+def test_delta_uniform_matches_oracle(dev, oracle, case):
+    if case == "fig5":
+        tr, E = _fig5_trace("fig5_moe.txt"), 8
+    elif case == "random":
+        tr, E = _random_trace(21, 5, 333, 2, 8), 8
+    elif case == "single_token":
+        tr, E = _random_trace(22, 4, 1, 2, 8), 8
+    elif case == "wide":
+        tr, E = _random_trace(23, 3, 700, 8, 64, sticky=0.3), 64
+    elif case == "long":
+        tr, E = _random_trace(24, 3, 70000, 2, 8), 8   # several chunks per layer
+    elif case == "collapsed":
+        tr, E = np.tile(np.array([[6, 1]], np.int32), (2, 50, 1)), 8
+    else:
+        tr, E = _random_trace(25, 2, 90, 2, 8), 8
+    L = tr.shape[0]
+    counts = torch.full((L, E), -1, dtype=torch.int64, device=dev)
+    delta = torch.full((L,), float("nan"), dtype=torch.float64, device=dev)
+    mean = torch.full((1,), float("nan"), dtype=torch.float64, device=dev)
+    tr_gpu = tr.copy()
+    if case == "stray":
+        tr_gpu[1, 7, 0] = -3   # entries outside [0, E) are ignored by the library (the oracle rejects them)
+        tr_gpu[0, 3, 1] = E
+    pkg.moe_delta_uniform(to_device(tr_gpu, dev), E, counts, delta, mean)
+    torch.cuda.synchronize()
+    r_mean, r_delta, r_counts = oracle.delta_uniform(tr, E)
+    if case == "stray":
+        r_counts[1, tr[1, 7, 0]] -= 1
+        r_counts[0, tr[0, 3, 1]] -= 1
+        assert np.array_equal(counts.cpu().numpy(), r_counts)
+        return
+    assert np.array_equal(counts.cpu().numpy(), r_counts)            # integer part bit-exact
+    # fp64 on both sides, the same operations in the same order
+    assert np.allclose(delta.cpu().numpy(), r_delta, rtol=1e-14, atol=1e-16)
+    assert abs(mean.item() - r_mean) <= 1e-14 * max(r_mean, 1e-30) + 1e-16
+    if case == "collapsed":
+        assert mean.item() == 1.5
+
+
 def test_stack_trace_feeds_the_trace_metrics(dev, oracle):
     cfg = wl.shrink(wl.CONFIGS["phone_stack"], d_model=256, d_ff=512, weight_std=0.05)
     n_layers, T = 6, 64
