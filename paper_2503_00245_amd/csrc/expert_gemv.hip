@@ -15,9 +15,20 @@
 // A segment whose matrix is shared by all experts (the shared dense base) is read once
 // per row, not once per pair: with a shared input vector its product is reused for every
 // pair; in COMBINE the pairs' inputs are pre-mixed with the gates (linearity).
-// A wave reads a matrix row with 16-byte loads, 1 KB per instruction, two in flight, takes
-// the matching slice of the input vector straight from L1/L2, and reduces with a 64-lane
-// butterfly.  Nothing is staged in LDS, so the weight stream starts at once.
+// A wave reads a matrix row with 16-byte loads, 1 KB per instruction, takes the matching slice
+// of the input vector straight from L1/L2, and reduces with a 64-lane butterfly.  Nothing is
+// staged in LDS, so the weight stream starts at once.
+//
+// Two kernels.  gemv_pairs_kernel serves the stages with one segment and a matrix of its own per
+// expert (every stage of a dense or purely decomposed expert): it walks the row chunk by chunk
+// with the pairs inside, so a wave has the chunks of two experts (and of both matrices of a
+// gate/up product) in flight at once -- eight 1 KB loads -- and reads a shared input vector once
+// per chunk.  A wave's share of a row is a few KB, so what the stage costs is the number of
+// dependent load round trips per wave, not the bytes: pair by pair and matrix by matrix the
+// gate/up stage took eight round trips and the down stage six; chunk-major they take two.
+// gemv_kernel is the general form (two segments, segments shared by all experts).
+#include <type_traits>
+
 #include "common.h"
 
 namespace moe {
@@ -309,17 +320,227 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_kernel(const GemvArgs a) {
     }
 }
 
+
+// ---- one segment, one matrix per expert: chunk-major over pairs -------------------------------
+enum { VS_SHARED = 0, VS_PAIR_ACT = 1, VS_PAIR_F32 = 2 };  // one activation-typed vector for all pairs / one per pair
+
+// Row results of one wave -> outputs.  Shared by the single-slice paths of both kernels' callers.
+template <typename T, int MODE>
+__device__ __forceinline__ void store_pair(const GemvArgs& a, int j, int row, float a0, float a1) {
+    if (MODE == GEMV_SWIGLU) {
+        store_hidden<T>(a, (size_t)j * a.rows + row, silu_f32(a0) * a1);
+    } else {
+        a.out0[(size_t)j * a.rows + row] = a0;
+        if (MODE == GEMV_DUAL) a.out1[(size_t)j * a.rows + row] = a1;
+    }
+}
+
+template <typename T, int MODE, int VS>
+__global__ __launch_bounds__(kGemvThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void gemv_pairs_kernel(const GemvArgs a) {
+    typedef Store<T> S;
+    typedef typename S::vec_t vec_t;
+    constexpr int VEC = S::VEC;
+    constexpr int CH = kWave * VEC;
+    constexpr bool DUAL = (MODE == GEMV_DUAL || MODE == GEMV_SWIGLU);
+    // chunks of one pair group in flight: 8 weight loads per wave either way (fp32 vectors, twice
+    // the registers per chunk, take half)
+    constexpr int UB = (DUAL || VS == VS_PAIR_F32) ? 2 : 4;
+    __shared__ float s_part[kGemvWaves][2 * kMaxExperts + 2];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int k = a.k;
+    const int slices = a.slices;
+    const int slice = wave % slices;
+    const int local_row = wave / slices;
+    const GemvSeg& g = a.seg[0];
+    const int n = g.n;
+    const int nfull = n / CH;
+    const int lo = lane * VEC;
+    const bool tail_lane = nfull * CH + lo < n;  // n is a multiple of VEC: a lane is wholly in or out
+    const bool two_vecs = DUAL && g.v1 != g.v0;
+
+    const int rows_per_block = kGemvWaves / slices;
+    const int row0 = (blockIdx.x * rows_per_block + local_row) * a.rows_per_wave;
+    for (int ri = 0; ri < a.rows_per_wave; ++ri) {
+        const int row = row0 + ri;
+        const bool active = row < a.rows;
+        float* part = s_part[wave];
+        float total = 0.f;  // COMBINE, single slice
+        // KJ pairs at a time: their chunk loads are issued together
+        auto group = [&](int j0, auto kj) {
+            constexpr int KJ = decltype(kj)::value;
+            const T* w0[KJ];
+            const T* w1[KJ];
+            const void* v0[KJ];
+            const void* v1[KJ];
+#pragma unroll
+            for (int q = 0; q < KJ; ++q) {
+                const int e = min(max(a.idx[j0 + q], 0), a.E - 1);
+                const size_t woff = (size_t)e * g.stride + (size_t)row * n;
+                w0[q] = static_cast<const T*>(g.W0) + woff;
+                w1[q] = DUAL ? static_cast<const T*>(g.W1) + woff : w0[q];
+                const size_t voff = (size_t)(j0 + q) * g.vstride * (VS == VS_PAIR_F32 ? 4 : sizeof(T));
+                v0[q] = static_cast<const char*>(g.v0) + voff;
+                v1[q] = DUAL ? static_cast<const char*>(g.v1) + voff : v0[q];
+            }
+            float acc0[KJ], acc1[KJ];
+#pragma unroll
+            for (int q = 0; q < KJ; ++q) acc0[q] = acc1[q] = 0.f;
+            // nu chunks c, c + slices, ...: every load of the batch is issued before the first sum
+            // (the scheduling barrier keeps the compiler from sinking each load to its use, which
+            // would leave one load in flight per wave)
+            auto chunks = [&](int c, auto nu) {
+                constexpr int NU = decltype(nu)::value;
+                constexpr int NV = VS == VS_SHARED ? 1 : KJ;          // vectors per chunk and product
+                constexpr int VL = VS == VS_PAIR_F32 ? VEC / 4 : 1;   // load instructions per vector chunk
+                typedef typename std::conditional<VS == VS_PAIR_F32, f32x4, vec_t>::type xv_t;
+                vec_t wa[NU][KJ], wb[DUAL ? NU : 1][DUAL ? KJ : 1];
+                xv_t xa[NU][NV][VL], xb[DUAL ? NU : 1][DUAL ? NV : 1][VL];
+#pragma unroll
+                for (int u = 0; u < NU; ++u)
+#pragma unroll
+                    for (int q = 0; q < KJ; ++q) {
+                        const int at = (c + u * slices) * CH + lo;
+                        wa[u][q] = __builtin_nontemporal_load(reinterpret_cast<const vec_t*>(w0[q] + at));
+                        if (DUAL) wb[u][q] = __builtin_nontemporal_load(reinterpret_cast<const vec_t*>(w1[q] + at));
+                    }
+#pragma unroll
+                for (int u = 0; u < NU; ++u)
+#pragma unroll
+                    for (int q = 0; q < NV; ++q) {
+                        const int at = (c + u * slices) * CH + lo;
+#pragma unroll
+                        for (int l = 0; l < VL; ++l) {
+                            if (VS == VS_PAIR_F32) {
+                                xa[u][q][l] = *reinterpret_cast<const xv_t*>(static_cast<const float*>(v0[q]) + at + 4 * l);
+                                if (DUAL) xb[u][q][l] = *reinterpret_cast<const xv_t*>(static_cast<const float*>(v1[q]) + at + 4 * l);
+                            } else {
+                                xa[u][q][l] = *reinterpret_cast<const xv_t*>(static_cast<const T*>(v0[q]) + at);
+                                if (DUAL) xb[u][q][l] = two_vecs ? *reinterpret_cast<const xv_t*>(static_cast<const T*>(v1[q]) + at) : xa[u][q][l];
+                            }
+                        }
+                    }
+#if defined(__HIP_DEVICE_COMPILE__)
+                __builtin_amdgcn_sched_group_barrier(0x020, NU * KJ * (DUAL ? 2 : 1) + NU * NV * VL * (DUAL ? 2 : 1), 0);
+#endif
+#pragma unroll
+                for (int u = 0; u < NU; ++u)
+#pragma unroll
+                    for (int q = 0; q < KJ; ++q) {
+                        const int qv = VS == VS_SHARED ? 0 : q;
+#pragma unroll
+                        for (int i = 0; i < VEC; ++i) {
+                            float x0, x1;
+                            if (VS == VS_PAIR_F32) {
+                                x0 = xa[u][qv][i / 4][i % 4];
+                                x1 = DUAL ? xb[u][qv][i / 4][i % 4] : 0.f;
+                            } else {
+                                x0 = S::to_f32(xa[u][qv][0][i]);
+                                x1 = DUAL ? S::to_f32(xb[u][qv][0][i]) : 0.f;
+                            }
+                            acc0[q] = fmaf(S::get(wa[u][q], i), x0, acc0[q]);
+                            if (DUAL) acc1[q] = fmaf(S::get(wb[u][q], i), x1, acc1[q]);
+                        }
+                    }
+            };
+            if (active) {
+                int c = slice;
+                for (; c + (UB - 1) * slices < nfull; c += UB * slices) chunks(c, std::integral_constant<int, UB>{});
+                for (; c < nfull; c += slices) chunks(c, std::integral_constant<int, 1>{});
+                if (c == nfull && tail_lane) chunks(nfull, std::integral_constant<int, 1>{});
+            }
+#pragma unroll
+            for (int q = 0; q < KJ; ++q) {
+                const int j = j0 + q;
+                const float s0 = wave_sum(acc0[q]);
+                const float s1 = DUAL ? wave_sum(acc1[q]) : 0.f;
+                if (slices > 1) {
+                    if (lane == 0) {
+                        part[2 + 2 * j] = s0;
+                        part[3 + 2 * j] = s1;
+                    }
+                } else if (MODE == GEMV_COMBINE) {
+                    total = fmaf(a.gate[j], s0, total);
+                } else if (lane == 0 && active) {
+                    store_pair<T, MODE>(a, j, row, s0, s1);
+                }
+            }
+        };
+        int j0 = 0;
+        for (; j0 + 2 <= k; j0 += 2) group(j0, std::integral_constant<int, 2>{});
+        if (j0 < k) group(j0, std::integral_constant<int, 1>{});
+
+        if (slices > 1) {  // rows_per_wave is 1 here: the barrier is reached once, by every wave
+            __syncthreads();
+            if (slice == 0 && active) {
+                // lane q sums value q (and q + 64) over the row's slices, in slice order
+                float sum_lo = 0.f, sum_hi = 0.f;
+                for (int sl = 0; sl < slices; ++sl) {
+                    if (lane >= 2 && lane < 2 + 2 * k) sum_lo += s_part[wave + sl][lane];
+                    if (lane + kWave < 2 + 2 * k) sum_hi += s_part[wave + sl][lane + kWave];
+                }
+                auto value = [&](int q) {
+                    return q < kWave ? __shfl(sum_lo, q, kWave) : __shfl(sum_hi, q - kWave, kWave);
+                };
+                if (MODE == GEMV_COMBINE) {
+                    float tot = 0.f;
+                    for (int j = 0; j < k; ++j) tot = fmaf(a.gate[j], value(2 + 2 * j), tot);
+                    total = tot;
+                } else {
+                    for (int j = 0; j < k; ++j) {
+                        const float a0 = value(2 + 2 * j), a1 = value(3 + 2 * j);
+                        if (lane == 0) store_pair<T, MODE>(a, j, row, a0, a1);
+                    }
+                }
+            }
+        }
+        if (MODE == GEMV_COMBINE && lane == 0 && active && slice == 0) {
+            if (a.residual) total += Store<T>::to_f32(static_cast<const T*>(a.residual)[row]);
+            static_cast<T*>(a.y)[row] = Store<T>::from_f32(total);
+        }
+    }
+}
+
 template <typename T>
 static int launch_gemv(GemvArgs& a, int mode, hipStream_t st) {
     const size_t lds = 0;
-    // enough waves that every CU holds tens of them: split rows over several waves when the
-    // stage has few rows, give a wave several rows when it has very many
-    const int want_waves = 256 * 16;
+    const GemvSeg& g = a.seg[0];
+    const bool dual = mode == GEMV_DUAL || mode == GEMV_SWIGLU;
+    // One segment with a matrix per expert: the chunk-major kernel, unless the stage is a large
+    // two-matrix one.  Measured per stage (events; old / chunk-major): 2048 x 5632 gate/up, 92 MB:
+    // 20.0 / 21.4 us (there the stage runs at the rate of a plain read, and the older kernel's
+    // eight waves per SIMD all fit the chip at once where the wider kernel's four do not);
+    // 1024 x 2816 gate/up, 23 MB: 12.2 / 10.9; rank-1024 factors of a 2048 x 5632 expert: 12.3 /
+    // 10.2, 15.0 / 15.2, 11.7 / 10.3, 9.6 / 7.5; 2048 x 5632 down + combine, 46 MB: 13.9 / 13.4.
+    const size_t stage_bytes = (size_t)a.k * a.rows * g.n * (dual ? 2 : 1) * sizeof(T);
+    const bool pairs = a.nseg == 1 && g.stride != 0 && (g.vstride != 0 || !g.v_is_f32) &&
+                       !(dual && stage_bytes > ((size_t)64 << 20));
+    // enough waves that every CU holds many of them: split rows over several waves when the
+    // stage has few rows, give a wave several rows when it has very many.  A wave of the
+    // chunk-major kernel keeps eight weight loads in flight, so half as many waves do.
+    const int want_waves = pairs ? 256 * 8 : 256 * 16;
     a.slices = 1;
     while (a.k < 63 && a.slices < kGemvWaves && a.rows * a.slices * 2 <= want_waves) a.slices *= 2;
     a.rows_per_wave = a.slices > 1 ? 1 : max(1, min(8, a.rows / (4 * want_waves)));
     const int rows_per_block = (kGemvWaves / a.slices) * a.rows_per_wave;
     dim3 grid((a.rows + rows_per_block - 1) / rows_per_block), block(kGemvThreads);
+    if (pairs) {
+        const int vs = g.vstride == 0 ? VS_SHARED : (g.v_is_f32 ? VS_PAIR_F32 : VS_PAIR_ACT);
+#define MOE_GEMV_PAIRS(M, V)                                                                        \
+    if (mode == M && vs == V) {                                                                    \
+        hipLaunchKernelGGL((gemv_pairs_kernel<T, M, V>), grid, block, lds, st, a);                 \
+        return launch_status();                                                                    \
+    }
+        MOE_GEMV_PAIRS(GEMV_DUAL, VS_SHARED)
+        MOE_GEMV_PAIRS(GEMV_SWIGLU, VS_SHARED)
+        MOE_GEMV_PAIRS(GEMV_SWIGLU, VS_PAIR_F32)
+        MOE_GEMV_PAIRS(GEMV_PLAIN, VS_PAIR_ACT)
+        MOE_GEMV_PAIRS(GEMV_PLAIN, VS_PAIR_F32)
+        MOE_GEMV_PAIRS(GEMV_COMBINE, VS_PAIR_ACT)
+        MOE_GEMV_PAIRS(GEMV_COMBINE, VS_PAIR_F32)
+#undef MOE_GEMV_PAIRS
+        return MOE_ERR_LAUNCH;  // unreachable: every (mode, vector kind) the stages use is listed
+    }
     switch (mode) {
         case GEMV_PLAIN:
             hipLaunchKernelGGL((gemv_kernel<T, GEMV_PLAIN>), grid, block, lds, st, a);

@@ -14,7 +14,13 @@ namespace moe {
 constexpr int kRouteWaves = 8;
 constexpr int kRouteTok = 2;  // tokens per workgroup
 
-template <typename T>
+#ifndef MOE_ROUTE_NB_LARGE
+#define MOE_ROUTE_NB_LARGE 2
+#endif
+// NB: router-row chunks a wave requests at once (4 for small batches, where the kernel is a chain
+// of memory round trips; fewer for large ones, where registers per wave decide how many
+// workgroups a CU holds)
+template <typename T, int NB>
 __global__ __launch_bounds__(kRouteWaves* kWave) void route_kernel(
     const T* __restrict__ x, const float* __restrict__ rw, const float* __restrict__ rb,
     int32_t* __restrict__ topk_idx, float* __restrict__ topk_gate, float* __restrict__ probs,
@@ -36,9 +42,11 @@ __global__ __launch_bounds__(kRouteWaves* kWave) void route_kernel(
     };
     for (int e = wave; e < E; e += kRouteWaves) {
         float acc[kRouteTok];
-        router_logits<VEC, kRouteTok>(load_x, rw + (size_t)e * d, d, lane, ntok, acc);
+        // (the bias is requested before the row is streamed: at a single token, with a cold router,
+        // a load issued only after the reduction is a second full memory round trip)
+        const float b = rb ? rb[e] : 0.f;
+        router_logits<VEC, kRouteTok, NB>(load_x, rw + (size_t)e * d, d, lane, ntok, acc);
         if (lane == 0) {
-            const float b = rb ? rb[e] : 0.f;
 #pragma unroll
             for (int t = 0; t < kRouteTok; ++t) s_logit[t][e] = acc[t] + b;
         }
@@ -152,12 +160,18 @@ int launch_route(const moe_shape& s, const void* x, const float* rw, const float
         return launch_route_lds<bf16_t>(s, (const bf16_t*)x, rw, rb, topk_idx, topk_gate, probs, st);
     }
     dim3 grid((s.n_tokens + kRouteTok - 1) / kRouteTok), block(kRouteWaves * kWave);
-    if (s.act_dtype == MOE_F32)
-        hipLaunchKernelGGL(route_kernel<float>, grid, block, 0, st, (const float*)x, rw, rb,
-                           topk_idx, topk_gate, probs, s.n_tokens, s.d_model, s.n_experts, s.top_k);
-    else
-        hipLaunchKernelGGL(route_kernel<bf16_t>, grid, block, 0, st, (const bf16_t*)x, rw, rb,
-                           topk_idx, topk_gate, probs, s.n_tokens, s.d_model, s.n_experts, s.top_k);
+    auto launch = [&](auto kern, auto* xp) {
+        hipLaunchKernelGGL(kern, grid, block, 0, st, xp, rw, rb, topk_idx, topk_gate, probs, s.n_tokens,
+                           s.d_model, s.n_experts, s.top_k);
+    };
+    const bool small = s.n_tokens <= 256;
+    if (s.act_dtype == MOE_F32) {
+        if (small) launch(route_kernel<float, 4>, (const float*)x);
+        else launch(route_kernel<float, MOE_ROUTE_NB_LARGE>, (const float*)x);
+    } else {
+        if (small) launch(route_kernel<bf16_t, 4>, (const bf16_t*)x);
+        else launch(route_kernel<bf16_t, MOE_ROUTE_NB_LARGE>, (const bf16_t*)x);
+    }
     return launch_status();
 }
 

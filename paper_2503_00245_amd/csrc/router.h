@@ -3,6 +3,8 @@
 // it so that every caller produces bit-identical logits, indices and gates.
 #pragma once
 
+#include <type_traits>
+
 #include "common.h"
 
 namespace moe {
@@ -10,39 +12,52 @@ namespace moe {
 // One wave, TOK tokens at once: logits <x_t, we> (the caller adds the bias).  Lane l takes
 // elements [l*VEC, l*VEC+VEC) of every 64*VEC-wide chunk; per token the fused multiply-adds
 // run in ascending index order and end in a 64-lane butterfly, so a token's logit does not
-// depend on TOK.  load_x(t, i, out) must yield x_t[i .. i+VEC) as floats; tokens t >= ntok
-// are skipped.  The router row is read once per chunk and reused for all TOK tokens.
-template <int VEC, int TOK, typename LoadX>
+// depend on TOK.  load_x(t, i, out) must yield x_t[i .. i+VEC) as floats; only tokens
+// t < ntok are ever asked for (the slots beyond re-read the last valid token and are ignored).  The router row is read once per chunk and reused for all TOK tokens.
+template <int VEC, int TOK, int NBATCH = 4, typename LoadX>
 __device__ __forceinline__ void router_logits(LoadX load_x, const float* __restrict__ we, int d,
                                               int lane, int ntok, float (&out)[TOK]) {
     float acc[TOK];
 #pragma unroll
     for (int t = 0; t < TOK; ++t) acc[t] = 0.f;
-    auto chunk = [&](int i) {
-        f32x4 wv[VEC / 4];
+    // NB chunks at once (NBATCH of them while that many are left): every load of the batch (router row and all TOK token rows; a token
+    // beyond ntok re-reads the last valid one, so no load is conditional) is issued before the
+    // first multiply-add.  Chunk by chunk, with a wait after each load, a single cold token paid
+    // eight dependent memory round trips for 12 KB.
+    auto batch = [&](int i0, auto nb) {
+        constexpr int NB = decltype(nb)::value;
+        constexpr int CHB = kWave * VEC;
+        f32x4 wv[NB][VEC / 4];
+        float xv[NB][TOK][VEC];
 #pragma unroll
-        for (int q = 0; q < VEC; q += 4) wv[q / 4] = *reinterpret_cast<const f32x4*>(we + i + q);
+        for (int b = 0; b < NB; ++b)
 #pragma unroll
-        for (int t = 0; t < TOK; ++t) {
-            if (t >= ntok) continue;
-            float xv[VEC];
-            load_x(t, i, xv);
+            for (int q = 0; q < VEC; q += 4) wv[b][q / 4] = *reinterpret_cast<const f32x4*>(we + i0 + b * CHB + q);
 #pragma unroll
-            for (int q = 0; q < VEC; q += 4) {
-                acc[t] = fmaf(xv[q + 0], wv[q / 4][0], acc[t]);
-                acc[t] = fmaf(xv[q + 1], wv[q / 4][1], acc[t]);
-                acc[t] = fmaf(xv[q + 2], wv[q / 4][2], acc[t]);
-                acc[t] = fmaf(xv[q + 3], wv[q / 4][3], acc[t]);
-            }
-        }
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int t = 0; t < TOK; ++t) load_x(min(t, ntok - 1), i0 + b * CHB, xv[b][t]);
+#if defined(__HIP_DEVICE_COMPILE__)
+        __builtin_amdgcn_sched_group_barrier(0x020, NB * (VEC / 4) + NB * TOK * (VEC == 8 ? 1 : VEC / 4), 0);
+#endif
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int t = 0; t < TOK; ++t)
+#pragma unroll
+                for (int q = 0; q < VEC; q += 4) {
+                    acc[t] = fmaf(xv[b][t][q + 0], wv[b][q / 4][0], acc[t]);
+                    acc[t] = fmaf(xv[b][t][q + 1], wv[b][q / 4][1], acc[t]);
+                    acc[t] = fmaf(xv[b][t][q + 2], wv[b][q / 4][2], acc[t]);
+                    acc[t] = fmaf(xv[b][t][q + 3], wv[b][q / 4][3], acc[t]);
+                }
     };
-    // whole 64-lane chunks have a wave-uniform trip count, so the compiler can unroll the loop
-    // and put several chunks' loads in flight; the ragged tail is one predicated chunk
     constexpr int CH = kWave * VEC;
     const int nfull = d / CH;
-#pragma unroll 4
-    for (int c = 0; c < nfull; ++c) chunk(c * CH + lane * VEC);
-    if (nfull * CH + lane * VEC < d) chunk(nfull * CH + lane * VEC);
+    int c = 0;
+    for (; c + NBATCH <= nfull; c += NBATCH) batch(c * CH + lane * VEC, std::integral_constant<int, NBATCH>{});
+    for (; c < nfull; ++c) batch(c * CH + lane * VEC, std::integral_constant<int, 1>{});
+    if (nfull * CH + lane * VEC < d) batch(nfull * CH + lane * VEC, std::integral_constant<int, 1>{});
 #pragma unroll
     for (int t = 0; t < TOK; ++t) out[t] = wave_sum(acc[t]);
 }
