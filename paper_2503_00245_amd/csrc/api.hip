@@ -57,7 +57,7 @@ static Workspace carve(const moe_shape& s) {
     ws.perm = take(P * sizeof(int32_t));
     ws.inv_perm = take(P * sizeof(int32_t));
     ws.sort_scratch = take(permute_scratch_bytes((int)P, s.n_experts));
-    ws.y_perm = take(P * s.d_model * elt_size(s.act_dtype));
+    ws.y_perm = take(P * s.d_model * elt_size(s.act_dtype) * down_parts_capacity(s));  // room for partial outputs
     ws.y_base = take(token_base_supported(s) ? (size_t)s.n_tokens * s.d_model * elt_size(s.act_dtype) : 0);
     ws.ffn_scratch = take(ffn_scratch_bytes(s));
     ws.decode_scratch = take(decode_scratch_bytes(s));
@@ -94,10 +94,11 @@ static int forward_impl(const moe_shape& s, const moe_weights& w, const void* x,
         stage_mark(timer, "combine");
         return rc;
     }
+    int y_parts = down_parts_capacity(s);  // the down projection may leave partial outputs for the combine to add
     rc = launch_expert_ffn(s, w, x, perm, s.top_k, offsets, wsp + ws.y_perm, wsp + ws.ffn_scratch, st,
-                           timer);
+                           timer, &y_parts);
     if (rc != MOE_OK) return rc;
-    rc = launch_combine(s, wsp + ws.y_perm, inv_perm, gate, residual, y, st);
+    rc = launch_combine(s, wsp + ws.y_perm, inv_perm, gate, residual, y, st, nullptr, y_parts);
     stage_mark(timer, "combine");
     return rc;
 }

@@ -132,17 +132,24 @@ int launch_permute(int P, int E, const int32_t* topk_idx, int32_t* offsets, int3
 int launch_gather_rows(const moe_shape& s, const int32_t* perm, const void* x, void* x_perm,
                        hipStream_t st);
 
-// addend: optional second per-token term [T, d] in the activation type (beside the residual)
+// addend: optional second per-token term [T, d] in the activation type (beside the residual).
+// y_parts > 1: y_perm holds that many partial outputs [P, d], one after the other, to be added.
 int launch_combine(const moe_shape& s, const void* y_perm, const int32_t* inv_perm,
                    const float* topk_gate, const void* residual, void* y, hipStream_t st,
-                   const void* addend = nullptr);
+                   const void* addend = nullptr, int y_parts = 1);
 
 // Grouped expert FFN on P sorted rows.  a_row_map/a_row_div: optional gather of the input
 // rows (row of sorted slot s is x[a_row_map[s] / a_row_div]); NULL = x is already grouped.
+// y_parts: NULL = y_perm is one output [P, d].  Otherwise *y_parts says how many outputs [P, d]
+// y_perm has room for (down_parts_capacity) and receives how many partial outputs, to be added
+// by the consumer, were written: the last product may cut its k-steps into parts to fill the chip.
+constexpr int kMaxDownParts = 4;
+int down_parts_capacity(const moe_shape& s);
 size_t ffn_scratch_bytes(const moe_shape& s);
 int launch_expert_ffn(const moe_shape& s, const moe_weights& w, const void* x,
                       const int32_t* a_row_map, int a_row_div, const int32_t* offsets,
-                      void* y_perm, void* scratch, hipStream_t st, StageTimer* timer = nullptr);
+                      void* y_perm, void* scratch, hipStream_t st, StageTimer* timer = nullptr,
+                      int* y_parts = nullptr);
 
 // Shared-base experts M_e = M0 + L_e R_e (Sec. 2.2, Eq. 1 with a base shared by all experts), prefill,
 // with the token of every sorted slot known: the base products run once per token instead

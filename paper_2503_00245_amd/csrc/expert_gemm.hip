@@ -26,6 +26,10 @@
 
 #include "common.h"
 
+#ifndef MOE_GEMM_HF
+#define MOE_GEMM_HF 1
+#endif
+
 namespace moe {
 
 template <int... I, typename F>
@@ -74,6 +78,12 @@ struct GemmArgs {
     int n_inner;        // tile order inside an expert: blocks of this many n-tiles (0 or 1: n-tile outer, m-tiles inner)
     int split_slots;    // workgroups one XCD runs at a time; > 0: the tiles of its last, partial round are cut
                         // into upper and lower halves when both halves still fit in one round (set by the launcher)
+    // PLAIN, one segment: the k-steps of every tile are cut into k_parts consecutive ranges, each
+    // computed by a workgroup of its own and stored to its own output [P, N] (part q at
+    // C + q * part_stride elements); whoever consumes C adds the parts.  In: the most parts the
+    // caller's output can take (0 or 1: none).  Out (set by run_gemm): the parts used.
+    int k_parts;
+    long long part_stride;
 };
 
 // Group e's row range; offsets == NULL means one group holding all P rows (a plain product).
@@ -236,11 +246,18 @@ __device__ __forceinline__ int lds_off(int row, int chunk) {
 // TAIL: K need not be a multiple of BK (a separate instantiation, so that the loop of the common
 // case carries none of the tail's bookkeeping: with it the down product of a 2048 x 5632 layer
 // measured 3.5 % slower).
+// HF ("half fills"): the LDS stages hold k-steps of BK = 64 -- a row's share of a step is one whole
+// 128-byte line, where a step of 32 asks for every line twice, half each time -- but a step is
+// filled in two halves by rows (the upper and the lower half of the A and of the B tile), half a
+// step apart, each through its own small register set.  Registers per thread are those of the
+// BK = 32 pipeline (two full BK = 64 sets do not fit beside a 64 x 128 wave tile's accumulators),
+// the barriers per k are halved, and every load instruction covers 8 rows x 128 bytes.
 template <int BM, int BN, int BK, int WM, int WN, bool SWIGLU, bool DUAL_A, int NS, int KG, bool ADD = false,
-          bool TAIL = false>
+          bool TAIL = false, bool HF = false>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KG) void gemm_bf16_deep_kernel(const GemmArgs g) {
     static_assert(!ADD || SWIGLU, "per-token addends belong to the SwiGLU epilogue");
     static_assert(!TAIL || KG == 1, "a K tail only without k-groups");
+    static_assert(!HF || (KG == 1 && NS == 2 && BK == 64), "half fills: 64-wide steps, two half sets, no k-groups");
     constexpr int WAVES_N = BN / WN;
     constexpr int NTHR = (BM / WM) * WAVES_N * 64;  // threads of one k-group
     constexpr int MT = WM / 32, NT = WN / 32;
@@ -260,6 +277,13 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KG) void gemm_bf16_dee
     // two plain products in one launch: the upper half of the n-tiles belongs to (A1, B1, C1)
     const bool second = !SWIGLU && g.C1 != nullptr && nt >= g.n_tiles / 2;
     if (second) nt -= g.n_tiles / 2;
+    // k-parts ride on the n-tile index: n-tiles [q * n_base, (q + 1) * n_base) are part q
+    int part = 0;
+    if (!SWIGLU && KG == 1 && g.k_parts > 1) {
+        const int n_base = g.n_tiles / g.k_parts;
+        part = nt / n_base;
+        nt -= part * n_base;
+    }
     const int n0 = nt * BN_OUT;
 
     const int kg = threadIdx.x / NTHR;   // k-group of this wave
@@ -305,8 +329,11 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KG) void gemm_bf16_dee
                 for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
     }
 
+    // passes (of RPP rows) one register set covers: all of a tile, or (HF) one half of it
+    constexpr int AP = HF ? AI / 2 : AI, BP = HF ? BI / 2 : BI;
+    static_assert(!HF || (AI % 2 == 0 && BI % 2 == 0), "half fills cut the fill passes in two");
     struct Regs {
-        bf16x8 a[AI], a1[DUAL_A ? AI : 1], b[BI];
+        bf16x8 a[AP], a1[DUAL_A ? AP : 1], b[BP];
     };
 
     for (int sidx = 0; sidx < g.nseg; ++sidx) {
@@ -315,20 +342,31 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KG) void gemm_bf16_dee
         const bool dual = DUAL_A && sg.A1 != sg.A0;
         const bf16_t* B0 = static_cast<const bf16_t*>(second ? sg.B1 : sg.B0) + (size_t)e * sg.strideB;
         const bf16_t* B1 = SWIGLU ? static_cast<const bf16_t*>(sg.B1) + (size_t)e * sg.strideB : B0;
-        const int nk = (K + BK * KG - 1) / (BK * KG);  // k-steps of this group (the same for every group)
-        const int k_begin = kg * nk * BK;
+        int nk = (K + BK * KG - 1) / (BK * KG);  // k-steps of this group (the same for every group)
+        int k_begin = kg * nk * BK;
+        if (!SWIGLU && KG == 1 && g.k_parts > 1) {  // this workgroup's share of the k-steps
+            const int s0 = nk * part / g.k_parts, s1 = nk * (part + 1) / g.k_parts;
+            k_begin = s0 * BK;
+            nk = s1 - s0;
+        }
         const int k_last = (nk - 1) * BK;    // relative to k_begin
         // K tail (TAIL: K % BK != 0, a multiple of 8): in the last k-step a thread whose 16-byte
         // chunk lies at or beyond K reads an earlier chunk of its row instead (in bounds) and zeroes
         // its registers before they go to LDS.  Which threads those are never changes (a thread
         // always loads the same chunk of a tile), so the loop pays one vector min per step.
         const int tail_kt = (TAIL && K % BK != 0) ? nk - 1 : -1;               // wave-uniform
-        const bool tail_dead = TAIL && k_last + ld_chunk * 8 >= K;              // per thread
+        const bool tail_dead = TAIL && k_begin + k_last + ld_chunk * 8 >= K;    // per thread (never in a k-part before the last)
         const int k_last_t = tail_dead ? max(k_last - BK, -(ld_chunk * 8)) : k_last;
 
-        const bf16_t* pa[AI];
-        const bf16_t* pa1[DUAL_A ? AI : 1];
-        const bf16_t* pb[BI];
+        // Where a thread's rows start.  HF keeps 32-bit byte offsets from wave-uniform bases (the
+        // load then takes a scalar base and one vector register; its launcher checks that every
+        // operand stays below 4 GB): eight 64-bit pointers are registers this kernel does not have.
+        typedef typename std::conditional<HF, unsigned, const bf16_t*>::type rowref_t;
+        rowref_t pa[AI];
+        rowref_t pa1[DUAL_A ? AI : 1];
+        rowref_t pb[BI];
+        const char* const a0_base = static_cast<const char*>(second ? sg.A1 : sg.A0);
+        const char* const a1_base = static_cast<const char*>(sg.A1);
         // (the row-map lookups of all of a thread's rows are issued together: one latency, not AI)
         int arow[AI];
 #pragma unroll
@@ -342,58 +380,79 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KG) void gemm_bf16_dee
 #pragma unroll
         for (int i = 0; i < AI; ++i) {
             const size_t off = (size_t)arow[i] * K + k_begin + ld_chunk * 8;
-            pa[i] = static_cast<const bf16_t*>(second ? sg.A1 : sg.A0) + off;
-            if (DUAL_A) pa1[i] = static_cast<const bf16_t*>(sg.A1) + off;
+            if constexpr (HF) {
+                pa[i] = (unsigned)(off * 2);
+                if (DUAL_A) pa1[i] = (unsigned)(off * 2);
+            } else {
+                pa[i] = static_cast<const bf16_t*>(second ? sg.A1 : sg.A0) + off;
+                if (DUAL_A) pa1[i] = static_cast<const bf16_t*>(sg.A1) + off;
+            }
         }
 #pragma unroll
         for (int i = 0; i < BI; ++i) {
             const int j = ld_row + RPP * i;
             const int n = min(SWIGLU ? n0 + (j % (BN / 2)) : n0 + j, g.N - 1);
-            pb[i] = ((SWIGLU && i >= BI / 2) ? B1 : B0) + (size_t)n * K + k_begin + ld_chunk * 8;
+            const size_t off = (size_t)n * K + k_begin + ld_chunk * 8;
+            if constexpr (HF)
+                pb[i] = (unsigned)(off * 2);
+            else
+                pb[i] = ((SWIGLU && i >= BI / 2) ? B1 : B0) + off;
         }
+        // one 16-byte chunk at k offset k0 (elements) of the row a reference stands for
+        auto ld16 = [&](const char* base, rowref_t ref, int k0) {
+            if constexpr (HF)
+                return *reinterpret_cast<const bf16x8*>(base + (size_t)k0 * 2 + ref);
+            else
+                return *reinterpret_cast<const bf16x8*>(ref + k0);
+        };
 
-        auto gload = [&](Regs& r, int k0) {
+        // half: which half of the tile's fill passes the set covers (HF; 0 otherwise)
+        auto gload = [&](Regs& r, int k0, int half = 0) {
 #pragma unroll
-            for (int i = 0; i < AI; ++i) {
-                r.a[i] = *reinterpret_cast<const bf16x8*>(pa[i] + k0);
-                if (DUAL_A && dual) r.a1[i] = *reinterpret_cast<const bf16x8*>(pa1[i] + k0);
+            for (int i = 0; i < AP; ++i) {
+                r.a[i] = ld16(a0_base, pa[half * AP + i], k0);
+                if (DUAL_A && dual) r.a1[i] = ld16(a1_base, pa1[half * AP + i], k0);
             }
 #pragma unroll
-            for (int i = 0; i < BI; ++i) r.b[i] = *reinterpret_cast<const bf16x8*>(pb[i] + k0);
+            for (int i = 0; i < BP; ++i) {
+                const int pass = half * BP + i;
+                r.b[i] = ld16(reinterpret_cast<const char*>((SWIGLU && pass >= BI / 2) ? B1 : B0), pb[pass], k0);
+            }
         };
         auto zero_dead = [&](Regs& r) {
             if (tail_dead) {
 #pragma unroll
-                for (int i = 0; i < AI; ++i) {
+                for (int i = 0; i < AP; ++i) {
                     r.a[i] = bf16x8{};
                     if (DUAL_A) r.a1[i] = bf16x8{};
                 }
 #pragma unroll
-                for (int i = 0; i < BI; ++i) r.b[i] = bf16x8{};
+                for (int i = 0; i < BP; ++i) r.b[i] = bf16x8{};
             }
         };
-        auto lstore = [&](int stage, const Regs& r) {
+        auto lstore = [&](int stage, const Regs& r, int half = 0) {
             char* base = gmem + stage * STAGE;
 #pragma unroll
-            for (int i = 0; i < AI; ++i) {
-                *reinterpret_cast<bf16x8*>(base + lds_off<BK>(ld_row + RPP * i, ld_chunk)) = r.a[i];
+            for (int i = 0; i < AP; ++i) {
+                const int row = ld_row + RPP * (half * AP + i);
+                *reinterpret_cast<bf16x8*>(base + lds_off<BK>(row, ld_chunk)) = r.a[i];
                 if (DUAL_A && dual)
-                    *reinterpret_cast<bf16x8*>(base + A_BYTES + lds_off<BK>(ld_row + RPP * i, ld_chunk)) = r.a1[i];
+                    *reinterpret_cast<bf16x8*>(base + A_BYTES + lds_off<BK>(row, ld_chunk)) = r.a1[i];
             }
             char* bb = base + A_BYTES * NA;
 #pragma unroll
-            for (int i = 0; i < BI; ++i)
-                *reinterpret_cast<bf16x8*>(bb + lds_off<BK>(ld_row + RPP * i, ld_chunk)) = r.b[i];
+            for (int i = 0; i < BP; ++i)
+                *reinterpret_cast<bf16x8*>(bb + lds_off<BK>(ld_row + RPP * (half * BP + i), ld_chunk)) = r.b[i];
         };
         // MA = how many of the wave's MT 32-row blocks hold rows of the group (the rest are skipped)
-        auto compute = [&](int stage, auto ma) {
+        auto compute = [&](int stage, auto ma, int ks_begin = 0, int ks_end = BK / 16) {
             constexpr int MA = decltype(ma)::value;
             const char* base = gmem + stage * STAGE;
             const char* a0b = base;
             const char* a1b = (DUAL_A && dual) ? base + A_BYTES : base;
             const char* bb = base + A_BYTES * NA;
 #pragma unroll
-            for (int ks = 0; ks < BK / 16; ++ks) {
+            for (int ks = ks_begin; ks < ks_end; ++ks) {
                 const int chunk = ks * 2 + (lane >> 5);
                 bf16x8 fa[MA], fa1[DUAL_A ? MA : 1], fb[NT];
 #pragma unroll
@@ -429,13 +488,31 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KG) void gemm_bf16_dee
         // tile kt+1 never also waits for the younger loads behind it.
         constexpr int UNR = (NS % 2 == 0) ? NS : 2 * NS;  // steps until (set, stage) repeat
         Regs r[NS];
+        if constexpr (HF) {
+            // r[0] / r[1] carry the upper / lower half of a tile: tile 0 goes to stage 0 through
+            // them, then they hold tile 1
+            gload(r[0], 0, 0);
+            gload(r[1], 0, 1);
+            if constexpr (TAIL) {
+                if (tail_kt == 0) {
+                    zero_dead(r[0]);
+                    zero_dead(r[1]);
+                }
+            }
+            __syncthreads();  // the previous segment's readers are done with both stages
+            lstore(0, r[0], 0);
+            gload(r[0], min(BK, k_last_t), 0);
+            lstore(0, r[1], 1);
+            gload(r[1], min(BK, k_last_t), 1);
+        } else {
 #pragma unroll
-        for (int q = 0; q < NS; ++q) gload(r[q], min(q * BK, k_last_t));
-        if constexpr (TAIL) {
-            if (tail_kt == 0) zero_dead(r[0]);
+            for (int q = 0; q < NS; ++q) gload(r[q], min(q * BK, k_last_t));
+            if constexpr (TAIL) {
+                if (tail_kt == 0) zero_dead(r[0]);
+            }
+            __syncthreads();  // the previous segment's readers are done with both stages
+            lstore(0, r[0]);
         }
-        __syncthreads();  // the previous segment's readers are done with both stages
-        lstore(0, r[0]);
         __syncthreads();
         // Issue order inside a step: the step's global loads and LDS writes are spread through
         // the MFMA sequence (one memory instruction in the shadow of each MFMA) instead of
@@ -460,6 +537,32 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KG) void gemm_bf16_dee
             }
 #endif
         };
+        // HF: a step writes the two halves of tile kt+1 to the other stage, the upper half at its
+        // start and the lower half in its middle, and refills each half's registers with tile
+        // kt+2 right after; memory instructions are spread one per two MFMAs in that order
+        auto interleave_hf = [&](auto ma) {
+#if defined(__HIP_DEVICE_COMPILE__)
+            constexpr int MA = decltype(ma)::value;
+            constexpr int NM = MA * NT * (BK / 16);           // MFMAs per step
+            constexpr int NR = (MA * NA + NT) * (BK / 16);    // LDS fragment reads per step
+            constexpr int NH = AP * NA + BP;                  // loads = LDS writes per half
+            constexpr int RPM = (NR + NM - 1) / NM;
+            constexpr int GAP = NM / (4 * NH) > 0 ? NM / (4 * NH) : 1;  // MFMAs per memory instruction
+            __builtin_amdgcn_sched_group_barrier(0x100, MA * NA + NT, 0);  // first fragments
+#pragma unroll
+            for (int i = 0; i < NM; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // one MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, RPM, 0);  // next fragments
+                if (i % GAP == 0) {
+                    const int op = i / GAP;  // 0 .. 4 NH - 1: writes of half 0, loads, writes of half 1, loads
+                    if (op < NH || (op >= 2 * NH && op < 3 * NH))
+                        __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+                    else if (op < 4 * NH)
+                        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                }
+            }
+#endif
+        };
         // The wave multiplies only those of its 32-row blocks that hold rows of the group.  A wave
         // with none keeps filling LDS and meeting the barriers but issues no fragment reads or
         // MFMAs, which leaves its SIMD and the LDS read port to the waves that do have rows.
@@ -470,6 +573,24 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KG) void gemm_bf16_dee
             // kt + 1 (set (S + 1) % NS) to the other stage
             auto step = [&](auto sc, int kt) {
                 constexpr int S = decltype(sc)::value;
+                if constexpr (HF) {
+                    if constexpr (TAIL) {
+                        if (kt + 1 == tail_kt) {  // both halves of the tile this step writes to LDS
+                            zero_dead(r[0]);
+                            zero_dead(r[1]);
+                        }
+                    }
+                    const int k_next = min((kt + 2) * BK, k_last_t);
+                    lstore((S & 1) ^ 1, r[0], 0);
+                    gload(r[0], k_next, 0);
+                    if constexpr (MA > 0) compute(S & 1, ma, 0, BK / 32);
+                    lstore((S & 1) ^ 1, r[1], 1);
+                    gload(r[1], k_next, 1);
+                    if constexpr (MA > 0) compute(S & 1, ma, BK / 32, BK / 16);
+                    if constexpr (MA > 0) interleave_hf(ma);
+                    __syncthreads();
+                    return;
+                }
                 if constexpr (TAIL) {
                     if (kt + 1 == tail_kt) zero_dead(r[(S + 1) % NS]);  // the tile this step writes to LDS
                 }
@@ -529,7 +650,8 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KG) void gemm_bf16_dee
     // ---- epilogue: accumulator element i of a 32x32 block sits at row (i/4)*8 + (lane/32)*4 + i%4,
     //      column lane%32 -------------------------------------------------------------------------
     // A block with no rows of the group is skipped.
-    bf16_t* const Ct = static_cast<bf16_t*>(second ? g.C1 : g.C) + (size_t)row0 * g.N + n0;  // wave-uniform
+    bf16_t* const Ct = static_cast<bf16_t*>(second ? g.C1 : g.C) + (size_t)part * g.part_stride +
+                       (size_t)row0 * g.N + n0;  // wave-uniform
     const unsigned ldc = (unsigned)g.N;
     if constexpr (KG == 1) {
         // Through LDS, so that the tile leaves in 16-byte stores (8 per wave and 32 x 64 block)
@@ -692,14 +814,15 @@ __global__ __launch_bounds__(256) void gemm_simple_kernel(const GemmArgs g) {
 }
 
 // ============================================================================= host side
-template <int BM, int BN, int BK, int WM, int WN, bool SWIGLU, bool DUAL_A, int NS = 2, int KG = 1, bool ADD = false>
+template <int BM, int BN, int BK, int WM, int WN, bool SWIGLU, bool DUAL_A, int NS = 2, int KG = 1, bool ADD = false,
+          bool HF = false>
 static int launch_bf16_deep(GemmArgs& g, hipStream_t st) {
     if ((g.add0 != nullptr) != ADD) return MOE_ERR_INVALID;
     constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;
     constexpr int NTHR = (BM / WM) * (BN / WN) * 64 * KG;
     static_assert(NTHR <= 1024, "workgroup size");
     g.m_tiles_max = g.P / BM + g.E;
-    g.n_tiles = (g.N + BN_OUT - 1) / BN_OUT * ((!SWIGLU && g.C1) ? 2 : 1);
+    g.n_tiles = (g.N + BN_OUT - 1) / BN_OUT * ((!SWIGLU && g.C1) ? 2 : 1) * (g.k_parts > 1 ? g.k_parts : 1);
     const int total = g.m_tiles_max * g.n_tiles;
     constexpr size_t lds = KG * 2 * ((size_t)BM * BK * 2 * (DUAL_A ? 2 : 1) + (size_t)BN * BK * 2);
     static_assert(lds <= 160 * 1024, "LDS stages exceed the CU's 160 KB");
@@ -731,9 +854,9 @@ static int launch_bf16_deep(GemmArgs& g, hipStream_t st) {
         return launch_status();
     };
     if constexpr (KG == 1) {
-        if (tail) return launch(gemm_bf16_deep_kernel<BM, BN, BK, WM, WN, SWIGLU, DUAL_A, NS, KG, ADD, true>, 1);
+        if (tail) return launch(gemm_bf16_deep_kernel<BM, BN, BK, WM, WN, SWIGLU, DUAL_A, NS, KG, ADD, true, HF>, 1);
     }
-    return launch(gemm_bf16_deep_kernel<BM, BN, BK, WM, WN, SWIGLU, DUAL_A, NS, KG, ADD, false>, 0);
+    return launch(gemm_bf16_deep_kernel<BM, BN, BK, WM, WN, SWIGLU, DUAL_A, NS, KG, ADD, false, HF>, 0);
 }
 
 template <typename T, bool SWIGLU>
@@ -779,8 +902,38 @@ static int run_gemm(const moe_shape& s, GemmArgs& g, bool swiglu, hipStream_t st
         // groups hold about 128 rows or fewer, and for a plain product with few tiles and a
         // long K two k-groups per workgroup (on 64 x 64 tiles when the groups average 24 rows or less: measured faster at 16, slower at 32).
         const long long big_tiles = (long long)(g.P / 256 + (g.E + 1) / 2) * ((n_eff + (swiglu ? 127 : 255)) / (swiglu ? 128 : 256));
+        // A plain product with tall groups but a narrow output has too few 256 x 256 tiles for 256
+        // CUs (the 2048-wide down projection of 4096 rows: 160), and 128 x 128 tiles move twice the
+        // operand bytes into the CUs.  If the consumer can add partial outputs, the k-steps of
+        // every tile are cut into 2-4 parts, each a workgroup's: choose the count that minimises
+        // rounds x (k-steps per part + about 12 k-steps of fixed cost per workgroup).
+        const int max_parts = g.k_parts;
+        g.k_parts = 0;
+        if (!swiglu && !g.C1 && !g.add0 && g.nseg == 1 && max_parts >= 2 && g.P >= 384 * g.E && big_tiles < 400 &&
+            g.seg[0].K % 32 == 0 && g.seg[0].K >= 32 * 64) {
+            const int steps = g.seg[0].K / 32;
+            long long best = 0;
+            for (int q = 2; q <= (max_parts < 4 ? max_parts : 4); ++q) {
+                const long long rounds = (big_tiles * q + 255) / 256;
+                const long long cost = rounds * (steps / q + 12);
+                if (g.k_parts == 0 || cost < best) {
+                    best = cost;
+                    g.k_parts = q;
+                }
+            }
+            // (one round of whole tiles on part of the chip may still be the cheaper)
+            if ((big_tiles + 255) / 256 * (steps + 12) <= best) g.k_parts = 0;
+#if MOE_GEMM_HF
+            if (g.k_parts > 1) return launch_bf16_deep<256, 256, 64, 64, 128, false, false, 2, 1, false, true>(g, st);
+#endif
+            if (g.k_parts > 1) return launch_bf16_deep<256, 256, 32, 64, 128, false, false>(g, st);
+        }
         if (g.P >= 384 * g.E && big_tiles >= 400) {  // enough 256 x 256 tiles to fill 256 CUs
             if (swiglu && g.add0) return launch_bf16_deep<256, 256, 32, 64, 128, true, true, 2, 1, true>(g, st);
+#if MOE_GEMM_HF
+            if (swiglu && !dual) return launch_bf16_deep<256, 256, 64, 64, 128, true, false, 2, 1, false, true>(g, st);
+            if (!swiglu) return launch_bf16_deep<256, 256, 64, 64, 128, false, false, 2, 1, false, true>(g, st);
+#endif
             if (swiglu)
                 return dual ? launch_bf16_deep<256, 256, 32, 64, 128, true, true>(g, st)
                             : launch_bf16_deep<256, 256, 32, 64, 128, true, false>(g, st);
@@ -809,6 +962,13 @@ static int run_gemm(const moe_shape& s, GemmArgs& g, bool swiglu, hipStream_t st
     return MOE_ERR_UNSUPPORTED;  // bf16 rows that are not whole 16-byte chunks (the entry points reject them)
 }
 
+// Partial outputs the final down projection of this shape may leave (room the caller provides):
+// only tall groups are ever cut along K (see run_gemm).
+int down_parts_capacity(const moe_shape& s) {
+    const long long P = (long long)s.n_tokens * s.top_k;
+    return (s.act_dtype == MOE_BF16 && P >= 384ll * s.n_experts) ? kMaxDownParts : 1;
+}
+
 // The per-token treatment of a shared base needs the deep bf16 kernels (every K a multiple of 8,
 // which the shape check of the entry points already demands) and pays only when a token has more
 // than one expert.
@@ -828,7 +988,7 @@ size_t ffn_scratch_bytes(const moe_shape& s) {
 
 int launch_expert_ffn(const moe_shape& s, const moe_weights& w, const void* x,
                       const int32_t* a_row_map, int a_row_div, const int32_t* offsets,
-                      void* y_perm, void* scratch, hipStream_t st, StageTimer* timer) {
+                      void* y_perm, void* scratch, hipStream_t st, StageTimer* timer, int* y_parts) {
     const int d = s.d_model, F = s.d_ff, r = s.rank, E = s.n_experts;
     const int P = s.n_tokens * s.top_k;
     if (P == 0) return MOE_OK;
@@ -879,7 +1039,13 @@ int launch_expert_ffn(const moe_shape& s, const moe_weights& w, const void* x,
         if (base) g.seg[ns++] = GemmSeg{h, h, w.w_down, w.w_down, r == 0 ? (long long)d * F : 0, F, 0};
         if (r > 0) g.seg[ns++] = GemmSeg{td, td, w.ld, w.ld, (long long)d * r, r, 0};
         g.nseg = ns; g.N = d; g.C = y_perm; g.n_inner = kHiddenOperandBlock;
+        // *y_parts in: how many outputs [P, d] the caller's y_perm has room for
+        if (y_parts) {
+            g.k_parts = *y_parts;
+            g.part_stride = (long long)P * d;
+        }
         if ((rc = run_gemm(s, g, false, st)) != MOE_OK) return rc;
+        if (y_parts) *y_parts = g.k_parts > 1 ? g.k_parts : 1;
         stage_mark(timer, "gemm_down");
     }
     return MOE_OK;

@@ -436,6 +436,42 @@ def test_forward_seeded_prefill_sweep(dev, oracle, d, F, E, k, r, base, T):
     _forward_case(dev, oracle, cfg, T, sample=256)
 
 
+@pytest.mark.parametrize("d,F,E,k,T", [
+    (256, 2048, 3, 2, 1500),   # 32 steps of 64 cut into 4 parts of 8
+    (256, 2080, 2, 1, 2000),   # 32 whole steps and a tail of 32: only the last part holds the tail
+    (512, 4128, 2, 2, 1100),   # 64.5 steps, two output tiles per row tile
+])
+def test_forward_down_projection_cut_along_k(dev, oracle, d, F, E, k, T):
+    # tall groups, a narrow output and a long K: the down projection's 256 x 256 tiles are too few
+    # for the chip, so moe_forward cuts every tile's k-steps into parts whose partial outputs the
+    # combine adds; the result must still match the oracle and the staged calls (one part) closely
+    cfg = _cfg(name="kp", d=d, F=F, E=E, k=k, dtype="bf16", seed=1200 + F, std=0.04)
+    w_np = wl.make_layer_weights(cfg, with_bias=False)
+    w_t = weights_to_device(w_np, dev)
+    _forward_case(dev, oracle, cfg, T, w_np, w_t, sample=300)
+    # staged calls on the same input
+    x_t = to_device(wl.make_inputs(cfg, T), dev)
+    y1, idx1, _ = _forward_gpu(dev, w_t, x_t, k, pkg.MOE_BF16)
+    shape = pkg.shape_for(w_t, T, k, pkg.MOE_BF16)
+    P = T * k
+    idx = torch.empty((T, k), dtype=torch.int32, device=dev)
+    gate = torch.empty((T, k), dtype=torch.float32, device=dev)
+    pkg.moe_route(shape, x_t, w_t["router_w"], None, idx, gate, None)
+    off = torch.empty(E + 1, dtype=torch.int32, device=dev)
+    perm = torch.empty(P, dtype=torch.int32, device=dev)
+    inv = torch.empty(P, dtype=torch.int32, device=dev)
+    xp = torch.empty((P, d), dtype=torch.bfloat16, device=dev)
+    pkg.moe_permute(shape, idx, off, perm, inv, x_t, xp, pkg.alloc_workspace(shape, dev))
+    yp = torch.empty_like(xp)
+    ffn_shape = pkg.shape_for(w_t, P, 1, pkg.MOE_BF16)
+    pkg.moe_expert_ffn(ffn_shape, pkg.make_weights(w_t), xp, off, yp, pkg.alloc_workspace(ffn_shape, dev))
+    y3 = torch.empty_like(x_t)
+    pkg.moe_combine(shape, yp, inv, gate, None, y3)
+    torch.cuda.synchronize()
+    assert np.array_equal(idx.cpu().numpy(), idx1)
+    assert rel_err(to_f64(y1), to_f64(y3)) < 1e-2  # parts are rounded to bf16 one by one
+
+
 @pytest.mark.parametrize("k,E,T", [(2, 8, 2), (2, 8, 37), (2, 8, 600), (3, 5, 150), (8, 8, 64), (2, 16, 9)])
 def test_forward_shared_base_once_per_token(dev, oracle, k, E, T):
     # bf16 layers with k > 1 take the path that applies the shared base once per token (plain
