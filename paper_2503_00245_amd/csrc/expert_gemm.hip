@@ -26,10 +26,6 @@
 
 #include "common.h"
 
-#ifndef MOE_GEMM_HF
-#define MOE_GEMM_HF 1
-#endif
-
 namespace moe {
 
 template <int... I, typename F>
@@ -818,6 +814,16 @@ template <int BM, int BN, int BK, int WM, int WN, bool SWIGLU, bool DUAL_A, int 
           bool HF = false>
 static int launch_bf16_deep(GemmArgs& g, hipStream_t st) {
     if ((g.add0 != nullptr) != ADD) return MOE_ERR_INVALID;
+    if constexpr (HF) {
+        // the half-fill kernel addresses rows by 32-bit byte offsets from the operand's base:
+        // an operand of 4 GB or more goes to the 32-wide pipeline with its 64-bit pointers
+        for (int i = 0; i < g.nseg; ++i) {
+            const GemmSeg& sg = g.seg[i];
+            const long long a_rows = sg.gather ? (g.P - 1) / (g.row_div > 0 ? g.row_div : 1) + 1 : g.P;
+            if (a_rows * sg.K * 2 >= (1ll << 32) || (long long)g.N * sg.K * 2 >= (1ll << 32))
+                return launch_bf16_deep<BM, BN, 32, WM, WN, SWIGLU, DUAL_A, NS, KG, ADD, false>(g, st);
+        }
+    }
     constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;
     constexpr int NTHR = (BM / WM) * (BN / WN) * 64 * KG;
     static_assert(NTHR <= 1024, "workgroup size");
@@ -894,23 +900,29 @@ static int run_gemm(const moe_shape& s, GemmArgs& g, bool swiglu, hipStream_t st
     if (s.act_dtype == MOE_F32)
         return swiglu ? launch_simple<float, true>(g, st) : launch_simple<float, false>(g, st);
     if (fast) {
-        // Tile choice, measured on the phone and wearables shapes with uniform and Zipf-skewed
-        // groups.  With about 400 or more rows per expert and a wide output, 256 x 256 x 32 tiles on
-        // 8 waves (64 x 128 per wave, two waves per SIMD) are fastest.  Below that the products
-        // are bound by streaming the weights, and what counts is enough workgroups to pull them
-        // with every CU: 128 x 128 x 64 tiles (two workgroups per CU), 64-row tiles once the
-        // groups hold about 128 rows or fewer, and for a plain product with few tiles and a
-        // long K two k-groups per workgroup (on 64 x 64 tiles when the groups average 24 rows or less: measured faster at 16, slower at 32).
-        const long long big_tiles = (long long)(g.P / 256 + (g.E + 1) / 2) * ((n_eff + (swiglu ? 127 : 255)) / (swiglu ? 128 : 256));
-        // A plain product with tall groups but a narrow output has too few 256 x 256 tiles for 256
-        // CUs (the 2048-wide down projection of 4096 rows: 160), and 128 x 128 tiles move twice the
-        // operand bytes into the CUs.  If the consumer can add partial outputs, the k-steps of
-        // every tile are cut into 2-4 parts, each a workgroup's: choose the count that minimises
-        // rounds x (k-steps per part + about 12 k-steps of fixed cost per workgroup).
+        // Tile choice, measured on the 2048 / 5632 and 1024 / 2816 shapes with uniform and Zipf-skewed
+        // groups, from 16 to 2048 tokens.  Enough 256 x 256 tiles to fill 256 CUs: those, on 8 waves
+        // (64 x 128 per wave, two waves per SIMD), with 64-wide k-steps filled in halves where the
+        // kernel has one activation operand.  Below that the products are bound by streaming the
+        // weights, and what counts is enough workgroups to pull them with every CU: 128 x 128 x 64
+        // tiles (two workgroups per CU), 64-row tiles once the groups hold about 128 rows or
+        // fewer, and for a plain product with few tiles and a long K two k-groups per workgroup
+        // (on 64 x 64 tiles while the groups average 64 rows or less).
+        const int n256 = (n_eff + (swiglu ? 127 : 255)) / (swiglu ? 128 : 256);
+        const long long big_tiles = (long long)(g.P / 256 + (g.E + 1) / 2) * n256;
+        // A plain product with a narrow output has too few 256 x 256 tiles for 256 CUs (the
+        // 2048-wide down projection of 4096 rows: 160), and smaller tiles move two to four times
+        // the operand bytes into the CUs.  If the consumer can add partial outputs, the k-steps
+        // of every tile are cut into 2-4 parts, each a workgroup's: the count that minimises
+        // rounds x (k-steps per part + about 12 k-steps of fixed cost per workgroup).  Worth it
+        // from about 24 rows per expert on, when four parts of every tile (one per expert at
+        // least) make some 220 workgroups: the 2048-wide down projection from 128 tokens on (45 us
+        // against 53, 79 against 111 at 1024 tokens, 116 against 142 at 2048), the 1024-wide one
+        // from 1024 tokens on.
         const int max_parts = g.k_parts;
         g.k_parts = 0;
-        if (!swiglu && !g.C1 && !g.add0 && g.nseg == 1 && max_parts >= 2 && g.P >= 384 * g.E && big_tiles < 400 &&
-            g.seg[0].K % 32 == 0 && g.seg[0].K >= 32 * 64) {
+        if (!swiglu && !g.C1 && !g.add0 && g.nseg == 1 && max_parts >= 2 && g.P > 24 * g.E && big_tiles < 400 &&
+            g.seg[0].K % 32 == 0 && g.seg[0].K >= 32 * 64 && (long long)(g.P / 256 + g.E) * n256 * 4 >= 224) {
             const int steps = g.seg[0].K / 32;
             long long best = 0;
             for (int q = 2; q <= (max_parts < 4 ? max_parts : 4); ++q) {
@@ -921,23 +933,14 @@ static int run_gemm(const moe_shape& s, GemmArgs& g, bool swiglu, hipStream_t st
                     g.k_parts = q;
                 }
             }
-            // (one round of whole tiles on part of the chip may still be the cheaper)
-            if ((big_tiles + 255) / 256 * (steps + 12) <= best) g.k_parts = 0;
-#if MOE_GEMM_HF
-            if (g.k_parts > 1) return launch_bf16_deep<256, 256, 64, 64, 128, false, false, 2, 1, false, true>(g, st);
-#endif
-            if (g.k_parts > 1) return launch_bf16_deep<256, 256, 32, 64, 128, false, false>(g, st);
+            return launch_bf16_deep<256, 256, 64, 64, 128, false, false, 2, 1, false, true>(g, st);
         }
+        if (swiglu && !dual && !g.add0 && g.P >= 128 * g.E && big_tiles >= 320)
+            return launch_bf16_deep<256, 256, 64, 64, 128, true, false, 2, 1, false, true>(g, st);
         if (g.P >= 384 * g.E && big_tiles >= 400) {  // enough 256 x 256 tiles to fill 256 CUs
             if (swiglu && g.add0) return launch_bf16_deep<256, 256, 32, 64, 128, true, true, 2, 1, true>(g, st);
-#if MOE_GEMM_HF
-            if (swiglu && !dual) return launch_bf16_deep<256, 256, 64, 64, 128, true, false, 2, 1, false, true>(g, st);
-            if (!swiglu) return launch_bf16_deep<256, 256, 64, 64, 128, false, false, 2, 1, false, true>(g, st);
-#endif
-            if (swiglu)
-                return dual ? launch_bf16_deep<256, 256, 32, 64, 128, true, true>(g, st)
-                            : launch_bf16_deep<256, 256, 32, 64, 128, true, false>(g, st);
-            return launch_bf16_deep<256, 256, 32, 64, 128, false, false>(g, st);
+            if (swiglu) return launch_bf16_deep<256, 256, 32, 64, 128, true, true>(g, st);  // two activation operands
+            return launch_bf16_deep<256, 256, 64, 64, 128, false, false, 2, 1, false, true>(g, st);
         }
         const bool small_groups = g.P <= 128 * g.E;
         if (swiglu && g.add0)
@@ -954,7 +957,10 @@ static int run_gemm(const moe_shape& s, GemmArgs& g, bool swiglu, hipStream_t st
         bool k_pairs = true;
         for (int i = 0; i < g.nseg; ++i) k_pairs &= g.seg[i].K % 128 == 0;
         if (tiles128 < 160 && k_pairs) {
-            if (g.P <= 24 * g.E) return launch_bf16_deep<64, 64, 64, 32, 32, false, false, 2, 2>(g, st);
+            // (64 x 64: the 1024-wide down projection at 16 rows per expert 16.4 us against 20.1 with
+            // 64 x 128, at 32 rows 17.2 against 21.1, at 64 rows 18.1 against 21.8, at 128 rows 24.6
+            // against 22.3)
+            if (g.P <= 64 * g.E) return launch_bf16_deep<64, 64, 64, 32, 32, false, false, 2, 2>(g, st);
             return launch_bf16_deep<64, 128, 64, 32, 64, false, false, 2, 2>(g, st);
         }
         return launch_bf16_deep<128, 128, 64, 64, 64, false, false>(g, st);
@@ -966,7 +972,7 @@ static int run_gemm(const moe_shape& s, GemmArgs& g, bool swiglu, hipStream_t st
 // only tall groups are ever cut along K (see run_gemm).
 int down_parts_capacity(const moe_shape& s) {
     const long long P = (long long)s.n_tokens * s.top_k;
-    return (s.act_dtype == MOE_BF16 && P >= 384ll * s.n_experts) ? kMaxDownParts : 1;
+    return (s.act_dtype == MOE_BF16 && P > 24ll * s.n_experts) ? kMaxDownParts : 1;
 }
 
 // The per-token treatment of a shared base needs the deep bf16 kernels (every K a multiple of 8,
