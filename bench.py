@@ -74,13 +74,21 @@ WORKLOADS = {
 
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of
 # this script (summaries under profiles/), each scaled by what the same counter reads for the 256 MiB
-# device copy of --pmc-calibration (FETCH_SIZE x2.0, WRITE_SIZE x1.0).  None: not measured.
-MEASURED_TRAFFIC_BYTES = {
-    # gemm_bf16_deep_kernel<256,256,32,64,128,SWIGLU>: 250283.2 KiB x 2.0 fetched + 45056.0 KiB written
-    "phone_prefill": int((250283.2 * 2.0 + 45056.0) * 1024),
-    # gemv_kernel<SWIGLU>: 45126.2 KiB x 2.0 fetched + 44.1 KiB written
-    "phone_decode": int((45126.2 * 2.0 + 44.1) * 1024),
+# device copy of --pmc-calibration (FETCH_SIZE x2.0, WRITE_SIZE x1.0).  TRAFFIC_SOURCE names, per workload,
+# the summary and the kernel line the figures are read from (a CPU test keeps the two in step).
+FETCH_SCALE, WRITE_SCALE = 2.0, 1.0
+TRAFFIC_SOURCE = {
+    # gate/up grouped GEMM with the SiLU * mul epilogue (256 x 256 tiles, 64-wide k-steps filled in halves)
+    "phone_prefill": ("phone_prefill_kernels_and_hbm_traffic.txt",
+                      r"gemm_bf16_deep_kernel<256, 256, 64, 64, 128, true, false"),
+    # gate/up matrix-vector products + SwiGLU of the single-token step
+    "phone_decode": ("phone_decode_kernels_and_hbm_traffic.txt", r"gemv_kernelIDF16bLi2E"),
 }
+MEASURED_KIB = {  # workload: (FETCH_SIZE mean, WRITE_SIZE mean), KiB per dispatch as the tool reports them
+    "phone_prefill": (287868.5, 46923.6),
+    "phone_decode": (45137.1, 44.0),
+}
+MEASURED_TRAFFIC_BYTES = {w: int((f * FETCH_SCALE + wr * WRITE_SCALE) * 1024) for w, (f, wr) in MEASURED_KIB.items()}
 
 
 def layer_weight_bytes(cfg):

@@ -69,3 +69,30 @@ def test_more_than_one_gpu_is_refused_with_a_message():
 def test_every_workload_names_a_known_configuration():
     for name, (cfg_name, tokens) in bench.WORKLOADS.items():
         assert cfg_name in wl.CONFIGS and tokens >= 1, name
+
+
+def _profile_means(fname, kernel_regex):
+    """(FETCH_SIZE mean, WRITE_SIZE mean) in KiB of the kernel's line in a committed profile summary."""
+    import re
+    section, found = None, {}
+    for ln in open(os.path.join(ROOT, "profiles", fname)):
+        if ln.startswith("== "):
+            section = "FETCH" if "FETCH_SIZE" in ln else "WRITE" if "WRITE_SIZE" in ln else None
+        elif section and re.search(kernel_regex, ln):
+            found[section] = float(re.search(r"mean\s+([\d.]+)", ln).group(1))
+    return found["FETCH"], found["WRITE"]
+
+
+def test_traffic_constants_are_the_committed_profiles_figures():
+    # roofline.traffic must not go stale when a kernel changes: the constants in bench.py are the
+    # counter means of the committed rocprofv3 summaries, scaled by the calibration copy's factors
+    assert set(bench.TRAFFIC_SOURCE) == set(bench.MEASURED_KIB)
+    for workload, (fname, regex) in bench.TRAFFIC_SOURCE.items():
+        fetch, write = _profile_means(fname, regex)
+        assert bench.MEASURED_KIB[workload] == (fetch, write), workload
+        assert bench.MEASURED_TRAFFIC_BYTES[workload] == int((fetch * 2.0 + write * 1.0) * 1024)
+    # and the calibration itself: the 256 MiB copy reads half its size on FETCH_SIZE, all of it on WRITE_SIZE
+    text = open(os.path.join(ROOT, "profiles", "phone_prefill_kernels_and_hbm_traffic.txt")).read()
+    import re
+    copies = re.findall(r"__amd_rocclr_copyBuffer.*max\s+([\d.]+)", text)
+    assert any(abs(float(c) - 131089) < 50 for c in copies) and any(float(c) == 262144.0 for c in copies)
