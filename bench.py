@@ -20,8 +20,8 @@ synchronisation; one JSON line is printed.
   preheat    untimed steps of the same workload run before the warm-up until the board has left its
              idle power state (at least 0.3 s, until two power readings 50 ms apart agree within 3 %,
              at most 2 s); without it the first milliseconds after idle run at a ramping clock
-  gpu_state  shader clock and board power from sysfs before the pre-heat, after it, while the timed
-             steps are executing (read after they are all enqueued) and after them
+  gpu_state  shader clock and board power from sysfs before the pre-heat, at its end (load on),
+             while an untimed repeat of the timed steps is executing, and after it
   configs    (default run only) the other benchmark configurations, measured briefly in the same
              process: ms per step, dominant-kernel and whole-layer roofline fractions
   decode     (default workload only) the same layer at one token per step: ms per step, tokens/s
@@ -160,7 +160,8 @@ def gpu_state():
 
 
 def preheat(step, sync, min_s=0.3, max_s=2.0):
-    """Run untimed steps until the board power has stopped climbing; returns (seconds, steps)."""
+    """Run untimed steps until the board power has stopped climbing; returns (seconds, steps, the
+    last clock / power sample, read while the load was on)."""
     t0 = time.perf_counter()
     n = 0
     last = None
@@ -179,7 +180,7 @@ def preheat(step, sync, min_s=0.3, max_s=2.0):
         if el >= min_s and (pw is None or (last is not None and abs(pw - last) <= 0.03 * max(pw, 1.0))):
             break
         last = pw
-    return time.perf_counter() - t0, n
+    return time.perf_counter() - t0, n, st or None
 
 
 def percentile(sorted_vals, q):
@@ -288,20 +289,27 @@ def main():
             del src, dst
 
         state_idle = gpu_state()
-        preheat_s, preheat_steps = preheat(step, torch.cuda.synchronize)
-        state_before = gpu_state()
+        # (no host work between the pre-heat and the warm-up: reading the power sensor takes
+        # milliseconds, long enough for the board to start leaving its loaded state)
+        preheat_s, preheat_steps, state_before = preheat(step, torch.cuda.synchronize)
         for i in range(warmup):
             step(i)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(steps):
             step(warmup + i)
-        state_during = gpu_state() if not brief else None  # the steps are enqueued and executing
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
         ms_per_step = elapsed / steps * 1e3
         tokens_per_s = T * steps / elapsed
-
+        # the same steps once more, untimed, with the clock and power read while they execute (the
+        # read itself takes longer than a short timed region, so it stays out of it)
+        state_during = None
+        if not brief:
+            for i in range(max(steps, 50)):
+                step(warmup + i)
+            state_during = gpu_state()
+            torch.cuda.synchronize()
         state_after = gpu_state()
 
         # ---- per-step latency spread: one event pair around every step --------------------------
