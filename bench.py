@@ -496,7 +496,7 @@ def main():
             n_sample = int(max(probe_n, min(T if not decode else 4096,
                                             probe_n * (args.cpu_seconds / 3.0) / max(probe, 1e-6))))
             if stack:
-                n_sample = max(1, min(n_sample, 2))
+                n_sample = max(1, min(n_sample, 32))
             if not (decode or stack):
                 n_sample = max(probe_n, n_sample // probe_n * probe_n)
             times = sorted(run_oracle(n_sample) for _ in range(3))

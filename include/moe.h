@@ -170,7 +170,7 @@ MOE_API int moe_forward(const moe_shape* shape, const moe_weights* weights, cons
  * call on a device).  The call allocates and frees nothing.
  *   - shapes whose moe_workspace_bytes() exceeds MOE_STATIC_WORKSPACE_BYTES are refused with
  *     MOE_ERR_WORKSPACE before any launch (single-token steps of every size fit; a 2048 / 5632
- *     layer up to about 230 tokens);
+ *     layer up to about 140 tokens);
  *   - every call on one GPU uses that GPU's one array: calls that overlap in time on the same GPU
  *     (two streams, two threads) race; calls on one stream, or otherwise ordered, are fine.
  *     Nothing in the array has to be cleared between calls.
