@@ -366,6 +366,12 @@ def main():
         stages = {n: stage_sum[n] / n_launch for n in order}
 
         kname, bound, work, unit = dominant_kernel_work(cfg, T)
+        if kname not in stages and "gemv_gate_up_swiglu" in stages:
+            # a few tokens on the matrix-vector path: bound by streaming the experts they selected (at
+            # most T k of them, each once) -- report against the upper bound of those bytes
+            n_sel = min(T * cfg.top_k, cfg.n_experts)
+            per = 2 * cfg.d_ff * (cfg.rank if cfg.rank else cfg.d_model) * 2
+            kname, bound, work, unit = "gemv_gate_up_swiglu", "hbm", float(n_sel * per), "GB/s"
         if kname not in stages:  # a shape the per-token base path does not take: base work per pair
             kname, work = "gemm_gate_up_swiglu", 4.0 * T * cfg.top_k * cfg.d_ff * (cfg.rank + cfg.d_model)
         kms = stages[kname]

@@ -149,8 +149,8 @@ MOE_API int moe_combine(const moe_shape* shape, const void* y_perm, const int32_
 
 /*
  * Whole layer: route -> dispatch -> expert FFN -> combine in one call, free to fuse
- * stages (single-token decode streams only the selected experts' weights as a
- * bandwidth-bound matrix-vector product; larger T runs a grouped MFMA GEMM).
+ * stages (a decode step of one or two tokens streams only the selected experts'
+ * weights as a bandwidth-bound matrix-vector product; larger T runs a grouped MFMA GEMM).
  * With a shared base (Sec. 2.2, M_e = M0 + L_e R_e) and k > 1 the shared matrices are
  * applied once per token, not once per (token, expert) pair: M0 x_t serves all of the
  * token's experts, and sum_j g_j M0 h_j = M0 (sum_j g_j h_j); the result equals the staged

@@ -50,6 +50,7 @@ struct GemvSeg {
     int v_is_f32;        // 1: fp32 scratch vector; 0: stored in the activation type
     int vstride;         // elements between pairs' vectors; 0 = same vector for every pair
     int n;               // row length
+    int vdiv;            // consecutive pairs that share one vector (a token's pairs share its row); 0 or 1: none
 };
 
 struct GemvArgs {
@@ -65,8 +66,9 @@ struct GemvArgs {
     float* out0;          // [k][rows]
     void* out0_act;       // SWIGLU: [k][rows] in the activation type, written instead of out0 (or NULL)
     float* out1;          // [k][rows] (DUAL)
-    void* y;              // [rows] activation type (COMBINE)
-    const void* residual; // [rows] or NULL (COMBINE)
+    void* y;              // [tokens][rows] activation type (COMBINE)
+    const void* residual; // [tokens][rows] or NULL (COMBINE)
+    int kk;               // pairs per token: the k pairs are k / kk tokens' (chunk-major kernel; 0 = one token)
 };
 
 // Where a stage's input vector comes from.  Vectors are read straight from global memory
@@ -358,6 +360,13 @@ __global__ __launch_bounds__(kGemvThreads) __attribute__((amdgpu_waves_per_eu(4,
     const int lo = lane * VEC;
     const bool tail_lane = nfull * CH + lo < n;  // n is a multiple of VEC: a lane is wholly in or out
     const bool two_vecs = DUAL && g.v1 != g.v0;
+    const int vdiv = g.vdiv > 1 ? g.vdiv : 1;
+    const int kk = a.kk > 0 ? a.kk : k;  // pairs per token; COMBINE writes one output row per token
+    // COMBINE: token t's output element of this row, from the gate-weighted sum of its pairs
+    auto store_token = [&](int t, int row, float total) {
+        if (a.residual) total += Store<T>::to_f32(static_cast<const T*>(a.residual)[(size_t)t * a.rows + row]);
+        static_cast<T*>(a.y)[(size_t)t * a.rows + row] = Store<T>::from_f32(total);
+    };
 
     const int rows_per_block = kGemvWaves / slices;
     const int row0 = (blockIdx.x * rows_per_block + local_row) * a.rows_per_wave;
@@ -365,7 +374,7 @@ __global__ __launch_bounds__(kGemvThreads) __attribute__((amdgpu_waves_per_eu(4,
         const int row = row0 + ri;
         const bool active = row < a.rows;
         float* part = s_part[wave];
-        float total = 0.f;  // COMBINE, single slice
+        float total = 0.f;  // COMBINE, single slice: the running sum of the current token's pairs
         // KJ pairs at a time: their chunk loads are issued together
         auto group = [&](int j0, auto kj) {
             constexpr int KJ = decltype(kj)::value;
@@ -379,7 +388,7 @@ __global__ __launch_bounds__(kGemvThreads) __attribute__((amdgpu_waves_per_eu(4,
                 const size_t woff = (size_t)e * g.stride + (size_t)row * n;
                 w0[q] = static_cast<const T*>(g.W0) + woff;
                 w1[q] = DUAL ? static_cast<const T*>(g.W1) + woff : w0[q];
-                const size_t voff = (size_t)(j0 + q) * g.vstride * (VS == VS_PAIR_F32 ? 4 : sizeof(T));
+                const size_t voff = (size_t)((j0 + q) / vdiv) * g.vstride * (VS == VS_PAIR_F32 ? 4 : sizeof(T));
                 v0[q] = static_cast<const char*>(g.v0) + voff;
                 v1[q] = DUAL ? static_cast<const char*>(g.v1) + voff : v0[q];
             }
@@ -461,6 +470,10 @@ __global__ __launch_bounds__(kGemvThreads) __attribute__((amdgpu_waves_per_eu(4,
                     }
                 } else if (MODE == GEMV_COMBINE) {
                     total = fmaf(a.gate[j], s0, total);
+                    if ((j + 1) % kk == 0) {  // the token's last pair
+                        if (lane == 0 && active) store_token(j / kk, row, total);
+                        total = 0.f;
+                    }
                 } else if (lane == 0 && active) {
                     store_pair<T, MODE>(a, j, row, s0, s1);
                 }
@@ -483,9 +496,11 @@ __global__ __launch_bounds__(kGemvThreads) __attribute__((amdgpu_waves_per_eu(4,
                     return q < kWave ? __shfl(sum_lo, q, kWave) : __shfl(sum_hi, q - kWave, kWave);
                 };
                 if (MODE == GEMV_COMBINE) {
-                    float tot = 0.f;
-                    for (int j = 0; j < k; ++j) tot = fmaf(a.gate[j], value(2 + 2 * j), tot);
-                    total = tot;
+                    for (int t = 0; t < k / kk; ++t) {
+                        float tot = 0.f;
+                        for (int j = t * kk; j < (t + 1) * kk; ++j) tot = fmaf(a.gate[j], value(2 + 2 * j), tot);
+                        if (lane == 0) store_token(t, row, tot);
+                    }
                 } else {
                     for (int j = 0; j < k; ++j) {
                         const float a0 = value(2 + 2 * j), a1 = value(3 + 2 * j);
@@ -493,10 +508,6 @@ __global__ __launch_bounds__(kGemvThreads) __attribute__((amdgpu_waves_per_eu(4,
                     }
                 }
             }
-        }
-        if (MODE == GEMV_COMBINE && lane == 0 && active && slice == 0) {
-            if (a.residual) total += Store<T>::to_f32(static_cast<const T*>(a.residual)[row]);
-            static_cast<T*>(a.y)[row] = Store<T>::from_f32(total);
         }
     }
 }
@@ -513,8 +524,10 @@ static int launch_gemv(GemvArgs& a, int mode, hipStream_t st) {
     // 1024 x 2816 gate/up, 23 MB: 12.2 / 10.9; rank-1024 factors of a 2048 x 5632 expert: 12.3 /
     // 10.2, 15.0 / 15.2, 11.7 / 10.3, 9.6 / 7.5; 2048 x 5632 down + combine, 46 MB: 13.9 / 13.4.
     const size_t stage_bytes = (size_t)a.k * a.rows * g.n * (dual ? 2 : 1) * sizeof(T);
+    const bool several = a.kk > 0 && a.kk < a.k;  // several tokens: only the chunk-major kernel knows them
     const bool pairs = a.nseg == 1 && g.stride != 0 && (g.vstride != 0 || !g.v_is_f32) &&
-                       !(dual && stage_bytes > ((size_t)64 << 20));
+                       (several || !(dual && stage_bytes > ((size_t)64 << 20)));
+    if (several && !pairs) return MOE_ERR_UNSUPPORTED;
     // enough waves that every CU holds many of them: split rows over several waves when the
     // stage has few rows, give a wave several rows when it has very many.  A wave of the
     // chunk-major kernel keeps eight weight loads in flight, so half as many waves do.
@@ -532,7 +545,9 @@ static int launch_gemv(GemvArgs& a, int mode, hipStream_t st) {
         return launch_status();                                                                    \
     }
         MOE_GEMV_PAIRS(GEMV_DUAL, VS_SHARED)
+        MOE_GEMV_PAIRS(GEMV_DUAL, VS_PAIR_ACT)
         MOE_GEMV_PAIRS(GEMV_SWIGLU, VS_SHARED)
+        MOE_GEMV_PAIRS(GEMV_SWIGLU, VS_PAIR_ACT)
         MOE_GEMV_PAIRS(GEMV_SWIGLU, VS_PAIR_F32)
         MOE_GEMV_PAIRS(GEMV_PLAIN, VS_PAIR_ACT)
         MOE_GEMV_PAIRS(GEMV_PLAIN, VS_PAIR_F32)
@@ -558,19 +573,34 @@ static int launch_gemv(GemvArgs& a, int mode, hipStream_t st) {
     return launch_status();
 }
 
-// scratch: h [k][F] fp32 (in the activation type once k F floats outgrow the L1), then (rank > 0) tg, tu, td [k][r] fp32
-size_t decode_scratch_bytes(const moe_shape& s) {
-    const size_t k = s.top_k;
-    return round_up(sizeof(float) * k * ((size_t)s.d_ff + 3 * (size_t)s.rank), 256);
+// Two tokens take the matrix-vector path too: their 2 k pairs are walked like one token's k, with
+// one output row per token (the kernel takes any number of tokens up to 64 pairs).  Every pair
+// streams its expert's rows from memory -- the weight loads are non-temporal, and pairs of different
+// tokens that chose the same expert are not neighbours -- so the step costs about 22 us per token
+// on the 2048 / 5632 layer: 60 us at two tokens against 69 for the grouped GEMM, which streams
+// each selected expert once, but 82 against 72 at three and 193 against 98 at eight.  Layers with
+// a shared base (whose per-row products serve one token) keep the grouped GEMM.
+constexpr int kMaxDecodeTokens = 2;
+bool decode_supported(const moe_shape& s) {
+    if (s.n_tokens == 1) return true;
+    return s.n_tokens <= kMaxDecodeTokens && (long long)s.n_tokens * s.top_k <= kMaxExperts &&
+           !(s.flags & MOE_FLAG_SHARED_BASE);
 }
 
-bool decode_supported(const moe_shape& s) { return s.n_tokens == 1; }
+// scratch: h [P][F] fp32 (in the activation type once P F floats outgrow the L1), then (rank > 0) tg, tu, td [P][r] fp32
+size_t decode_scratch_bytes(const moe_shape& s) {
+    const size_t P = decode_supported(s) ? (size_t)s.n_tokens * s.top_k : (size_t)s.top_k;
+    return round_up(sizeof(float) * P * ((size_t)s.d_ff + 3 * (size_t)s.rank), 256);
+}
 
 template <typename T>
 static int decode_ffn_t(const moe_shape& s, const moe_weights& w, const void* x,
                         const int32_t* idx, const float* gate, void* y, void* scratch,
                         hipStream_t st, StageTimer* timer) {
-    const int d = s.d_model, F = s.d_ff, r = s.rank, k = s.top_k;
+    // k: all (token, slot) pairs of the step; kk of them per token.  One token: its input vector is
+    // shared by every pair (vstride 0); several: pair p reads token p / kk's row (vdiv).
+    const int d = s.d_model, F = s.d_ff, r = s.rank, kk = s.top_k, k = s.n_tokens * s.top_k;
+    const int xs = s.n_tokens > 1 ? d : 0, xdiv = s.n_tokens > 1 ? kk : 0;
     const bool base = (r == 0) || (s.flags & MOE_FLAG_SHARED_BASE);
     const long long base_stride_gu = (r == 0) ? (long long)F * d : 0;  // shared base: stride 0
     float* h = static_cast<float*>(scratch);
@@ -589,18 +619,18 @@ static int decode_ffn_t(const moe_shape& s, const moe_weights& w, const void* x,
     if (r > 0) {  // rank-r inputs of the gate and up factors: tg = R_g x, tu = R_u x
         a = GemvArgs{};
         a.nseg = 1;
-        a.seg[0] = GemvSeg{w.rg, w.ru, (long long)r * d, x, x, 0, 0, d};
-        a.rows = r; a.k = k; a.E = s.n_experts; a.idx = idx; a.gate = gate; a.out0 = tg; a.out1 = tu;
+        a.seg[0] = GemvSeg{w.rg, w.ru, (long long)r * d, x, x, 0, xs, d, xdiv};
+        a.rows = r; a.k = k; a.kk = kk; a.E = s.n_experts; a.idx = idx; a.gate = gate; a.out0 = tg; a.out1 = tu;
         if ((rc = launch_gemv<T>(a, GEMV_DUAL, st)) != MOE_OK) return rc;
         stage_mark(timer, "gemv_rank_gate_up");
     }
     {  // hidden vector h_j = silu(M_gate x) * (M_up x)
         a = GemvArgs{};
         int ns = 0;
-        if (base) a.seg[ns++] = GemvSeg{w.w_gate, w.w_up, base_stride_gu, x, x, 0, 0, d};
+        if (base) a.seg[ns++] = GemvSeg{w.w_gate, w.w_up, base_stride_gu, x, x, 0, xs, d, xdiv};
         if (r > 0) a.seg[ns++] = GemvSeg{w.lg, w.lu, (long long)F * r, tg, tu, 1, r, r};
         a.nseg = ns;
-        a.rows = F; a.k = k; a.E = s.n_experts; a.idx = idx; a.gate = gate; a.out0 = h;
+        a.rows = F; a.k = k; a.kk = kk; a.E = s.n_experts; a.idx = idx; a.gate = gate; a.out0 = h;
         if (h_act) a.out0_act = h;
         if ((rc = launch_gemv<T>(a, GEMV_SWIGLU, st)) != MOE_OK) return rc;
         stage_mark(timer, "gemv_gate_up_swiglu");
@@ -609,7 +639,7 @@ static int decode_ffn_t(const moe_shape& s, const moe_weights& w, const void* x,
         a = GemvArgs{};
         a.nseg = 1;
         a.seg[0] = GemvSeg{w.rd, nullptr, (long long)r * F, h, h, h_act ? 0 : 1, F, F};
-        a.rows = r; a.k = k; a.E = s.n_experts; a.idx = idx; a.gate = gate; a.out0 = td;
+        a.rows = r; a.k = k; a.kk = kk; a.E = s.n_experts; a.idx = idx; a.gate = gate; a.out0 = td;
         if ((rc = launch_gemv<T>(a, GEMV_PLAIN, st)) != MOE_OK) return rc;
         stage_mark(timer, "gemv_rank_down");
     }
@@ -619,7 +649,7 @@ static int decode_ffn_t(const moe_shape& s, const moe_weights& w, const void* x,
         if (base) a.seg[ns++] = GemvSeg{w.w_down, nullptr, (r == 0) ? (long long)d * F : 0, h, h, h_act ? 0 : 1, F, F};
         if (r > 0) a.seg[ns++] = GemvSeg{w.ld, nullptr, (long long)d * r, td, td, 1, r, r};
         a.nseg = ns;
-        a.rows = d; a.k = k; a.E = s.n_experts; a.idx = idx; a.gate = gate; a.y = y;
+        a.rows = d; a.k = k; a.kk = kk; a.E = s.n_experts; a.idx = idx; a.gate = gate; a.y = y;
         a.residual = (s.flags & MOE_FLAG_RESIDUAL) ? x : nullptr;
         if ((rc = launch_gemv<T>(a, GEMV_COMBINE, st)) != MOE_OK) return rc;
         stage_mark(timer, "gemv_down_combine");

@@ -459,6 +459,32 @@ def test_forward_replayed_from_a_hip_graph_matches_eager(dev, static):
             assert torch.equal(yo, ye)
 
 
+@pytest.mark.parametrize("T", [2, 3, 5, 8])
+def test_forward_phone_config_few_tokens(dev, oracle, phone, T):
+    # two tokens take the matrix-vector path (their pairs are walked like one token's), three and
+    # more the grouped GEMM with a row or two per expert
+    cfg, w_np, w_t = phone
+    _forward_case(dev, oracle, cfg, T, w_np, w_t)
+    _forward_case(dev, oracle, cfg, T, w_np, w_t, residual=True)
+
+
+@pytest.mark.parametrize("name,T", [("phone_wd", 2), ("phone_wd", 7), ("phone_wd_base", 2)])
+def test_forward_weight_decomposed_few_tokens(dev, oracle, name, T):
+    # pure L R experts: four matrix-vector stages with per-token and per-pair inputs; a shared base
+    # keeps the grouped GEMM at these sizes
+    cfg = wl.CONFIGS[name]
+    _forward_case(dev, oracle, cfg, T)
+
+
+@pytest.mark.parametrize("k,E,T,dtype", [(32, 64, 2, "bf16"), (33, 64, 2, "bf16"), (3, 5, 2, "f32"), (1, 4, 2, "bf16"),
+                                         (7, 9, 2, "bf16"), (8, 64, 3, "bf16")])
+def test_forward_few_tokens_pair_limits(dev, oracle, k, E, T, dtype):
+    # two tokens on the matrix-vector path: 64 pairs is the most it takes (2 x 33 go to the grouped
+    # GEMM); odd k makes a group of two pairs span both tokens; k = 1 is one pair per token
+    cfg = _cfg(name=f"ft{k}{E}", d=264, F=520, E=E, k=k, dtype=dtype, seed=1300 + k + E + T, std=0.05)
+    _forward_case(dev, oracle, cfg, T, residual=bool(T % 2))
+
+
 @pytest.mark.parametrize("name", ["phone_wd", "phone_wd_base"])
 def test_forward_phone_weight_decomposed_configs(dev, oracle, name):
     cfg = wl.CONFIGS[name]
