@@ -337,7 +337,9 @@ __device__ __forceinline__ void store_pair(const GemvArgs& a, int j, int row, fl
     }
 }
 
-template <typename T, int MODE, int VS>
+// SEVERAL: the k pairs belong to k / kk tokens (a separate instantiation: the single token's
+// kernel carries none of the per-token bookkeeping, which cost its down + combine stage 4-7 %)
+template <typename T, int MODE, int VS, bool SEVERAL>
 __global__ __launch_bounds__(kGemvThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void gemv_pairs_kernel(const GemvArgs a) {
     typedef Store<T> S;
     typedef typename S::vec_t vec_t;
@@ -360,8 +362,8 @@ __global__ __launch_bounds__(kGemvThreads) __attribute__((amdgpu_waves_per_eu(4,
     const int lo = lane * VEC;
     const bool tail_lane = nfull * CH + lo < n;  // n is a multiple of VEC: a lane is wholly in or out
     const bool two_vecs = DUAL && g.v1 != g.v0;
-    const int vdiv = g.vdiv > 1 ? g.vdiv : 1;
-    const int kk = a.kk > 0 ? a.kk : k;  // pairs per token; COMBINE writes one output row per token
+    const int vdiv = SEVERAL && g.vdiv > 1 ? g.vdiv : 1;
+    const int kk = SEVERAL && a.kk > 0 ? a.kk : k;  // pairs per token; COMBINE writes one output row per token
     // COMBINE: token t's output element of this row, from the gate-weighted sum of its pairs
     auto store_token = [&](int t, int row, float total) {
         if (a.residual) total += Store<T>::to_f32(static_cast<const T*>(a.residual)[(size_t)t * a.rows + row]);
@@ -375,6 +377,13 @@ __global__ __launch_bounds__(kGemvThreads) __attribute__((amdgpu_waves_per_eu(4,
         const bool active = row < a.rows;
         float* part = s_part[wave];
         float total = 0.f;  // COMBINE, single slice: the running sum of the current token's pairs
+        // One token: the residual element this wave will add is requested now, ahead of the weight
+        // stream (asked for at the end, its latency would be the wave's last wait).
+        float res0 = 0.f;
+        if constexpr (MODE == GEMV_COMBINE && !SEVERAL) {
+            if (a.residual && lane == 0 && active && slice == 0)
+                res0 = Store<T>::to_f32(static_cast<const T*>(a.residual)[row]);
+        }
         // KJ pairs at a time: their chunk loads are issued together
         auto group = [&](int j0, auto kj) {
             constexpr int KJ = decltype(kj)::value;
@@ -388,13 +397,16 @@ __global__ __launch_bounds__(kGemvThreads) __attribute__((amdgpu_waves_per_eu(4,
                 const size_t woff = (size_t)e * g.stride + (size_t)row * n;
                 w0[q] = static_cast<const T*>(g.W0) + woff;
                 w1[q] = DUAL ? static_cast<const T*>(g.W1) + woff : w0[q];
-                const size_t voff = (size_t)((j0 + q) / vdiv) * g.vstride * (VS == VS_PAIR_F32 ? 4 : sizeof(T));
+                const size_t voff = (size_t)(SEVERAL ? (j0 + q) / vdiv : j0 + q) * g.vstride * (VS == VS_PAIR_F32 ? 4 : sizeof(T));
                 v0[q] = static_cast<const char*>(g.v0) + voff;
                 v1[q] = DUAL ? static_cast<const char*>(g.v1) + voff : v0[q];
             }
-            float acc0[KJ], acc1[KJ];
+            float acc0[KJ], acc1[KJ], gq[KJ];
 #pragma unroll
-            for (int q = 0; q < KJ; ++q) acc0[q] = acc1[q] = 0.f;
+            for (int q = 0; q < KJ; ++q) {
+                acc0[q] = acc1[q] = 0.f;
+                gq[q] = MODE == GEMV_COMBINE ? a.gate[j0 + q] : 0.f;  // with the expert ids, not after the stream
+            }
             // nu chunks c, c + slices, ...: every load of the batch is issued before the first sum
             // (the scheduling barrier keeps the compiler from sinking each load to its use, which
             // would leave one load in flight per wave)
@@ -469,10 +481,12 @@ __global__ __launch_bounds__(kGemvThreads) __attribute__((amdgpu_waves_per_eu(4,
                         part[3 + 2 * j] = s1;
                     }
                 } else if (MODE == GEMV_COMBINE) {
-                    total = fmaf(a.gate[j], s0, total);
-                    if ((j + 1) % kk == 0) {  // the token's last pair
-                        if (lane == 0 && active) store_token(j / kk, row, total);
-                        total = 0.f;
+                    total = fmaf(gq[q], s0, total);
+                    if constexpr (SEVERAL) {
+                        if ((j + 1) % kk == 0) {  // the token's last pair
+                            if (lane == 0 && active) store_token(j / kk, row, total);
+                            total = 0.f;
+                        }
                     }
                 } else if (lane == 0 && active) {
                     store_pair<T, MODE>(a, j, row, s0, s1);
@@ -496,10 +510,16 @@ __global__ __launch_bounds__(kGemvThreads) __attribute__((amdgpu_waves_per_eu(4,
                     return q < kWave ? __shfl(sum_lo, q, kWave) : __shfl(sum_hi, q - kWave, kWave);
                 };
                 if (MODE == GEMV_COMBINE) {
-                    for (int t = 0; t < k / kk; ++t) {
+                    if constexpr (SEVERAL) {
+                        for (int t = 0; t < k / kk; ++t) {
+                            float tot = 0.f;
+                            for (int j = t * kk; j < (t + 1) * kk; ++j) tot = fmaf(a.gate[j], value(2 + 2 * j), tot);
+                            if (lane == 0) store_token(t, row, tot);
+                        }
+                    } else {
                         float tot = 0.f;
-                        for (int j = t * kk; j < (t + 1) * kk; ++j) tot = fmaf(a.gate[j], value(2 + 2 * j), tot);
-                        if (lane == 0) store_token(t, row, tot);
+                        for (int j = 0; j < k; ++j) tot = fmaf(a.gate[j], value(2 + 2 * j), tot);
+                        total = tot;
                     }
                 } else {
                     for (int j = 0; j < k; ++j) {
@@ -508,6 +528,10 @@ __global__ __launch_bounds__(kGemvThreads) __attribute__((amdgpu_waves_per_eu(4,
                     }
                 }
             }
+        }
+        if constexpr (!SEVERAL) {
+            if (MODE == GEMV_COMBINE && lane == 0 && active && slice == 0)
+                static_cast<T*>(a.y)[row] = Store<T>::from_f32(total + res0);
         }
     }
 }
@@ -539,20 +563,26 @@ static int launch_gemv(GemvArgs& a, int mode, hipStream_t st) {
     dim3 grid((a.rows + rows_per_block - 1) / rows_per_block), block(kGemvThreads);
     if (pairs) {
         const int vs = g.vstride == 0 ? VS_SHARED : (g.v_is_f32 ? VS_PAIR_F32 : VS_PAIR_ACT);
-#define MOE_GEMV_PAIRS(M, V)                                                                        \
-    if (mode == M && vs == V) {                                                                    \
-        hipLaunchKernelGGL((gemv_pairs_kernel<T, M, V>), grid, block, lds, st, a);                 \
+#define MOE_GEMV_PAIRS(M, V, SEV)                                                                   \
+    if (mode == M && vs == V && several == SEV) {                                                  \
+        hipLaunchKernelGGL((gemv_pairs_kernel<T, M, V, SEV>), grid, block, lds, st, a);            \
         return launch_status();                                                                    \
     }
-        MOE_GEMV_PAIRS(GEMV_DUAL, VS_SHARED)
-        MOE_GEMV_PAIRS(GEMV_DUAL, VS_PAIR_ACT)
-        MOE_GEMV_PAIRS(GEMV_SWIGLU, VS_SHARED)
-        MOE_GEMV_PAIRS(GEMV_SWIGLU, VS_PAIR_ACT)
-        MOE_GEMV_PAIRS(GEMV_SWIGLU, VS_PAIR_F32)
-        MOE_GEMV_PAIRS(GEMV_PLAIN, VS_PAIR_ACT)
-        MOE_GEMV_PAIRS(GEMV_PLAIN, VS_PAIR_F32)
-        MOE_GEMV_PAIRS(GEMV_COMBINE, VS_PAIR_ACT)
-        MOE_GEMV_PAIRS(GEMV_COMBINE, VS_PAIR_F32)
+        // one token: its row is every pair's input (shared); several: a row per kk pairs
+        MOE_GEMV_PAIRS(GEMV_DUAL, VS_SHARED, false)
+        MOE_GEMV_PAIRS(GEMV_DUAL, VS_PAIR_ACT, true)
+        MOE_GEMV_PAIRS(GEMV_SWIGLU, VS_SHARED, false)
+        MOE_GEMV_PAIRS(GEMV_SWIGLU, VS_PAIR_ACT, true)
+        MOE_GEMV_PAIRS(GEMV_SWIGLU, VS_PAIR_F32, false)
+        MOE_GEMV_PAIRS(GEMV_SWIGLU, VS_PAIR_F32, true)
+        MOE_GEMV_PAIRS(GEMV_PLAIN, VS_PAIR_ACT, false)
+        MOE_GEMV_PAIRS(GEMV_PLAIN, VS_PAIR_ACT, true)
+        MOE_GEMV_PAIRS(GEMV_PLAIN, VS_PAIR_F32, false)
+        MOE_GEMV_PAIRS(GEMV_PLAIN, VS_PAIR_F32, true)
+        MOE_GEMV_PAIRS(GEMV_COMBINE, VS_PAIR_ACT, false)
+        MOE_GEMV_PAIRS(GEMV_COMBINE, VS_PAIR_ACT, true)
+        MOE_GEMV_PAIRS(GEMV_COMBINE, VS_PAIR_F32, false)
+        MOE_GEMV_PAIRS(GEMV_COMBINE, VS_PAIR_F32, true)
 #undef MOE_GEMV_PAIRS
         return MOE_ERR_LAUNCH;  // unreachable: every (mode, vector kind) the stages use is listed
     }
