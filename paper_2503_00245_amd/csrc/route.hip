@@ -12,7 +12,9 @@
 namespace moe {
 
 constexpr int kRouteWaves = 8;
-constexpr int kRouteTok = 2;  // tokens per workgroup
+constexpr int kRouteTok = 2;       // tokens per workgroup
+constexpr int kRouteTokLarge = 4;  // ... from kRouteLargeFrom tokens on
+constexpr int kRouteLargeFrom = 1024;
 
 #ifndef MOE_ROUTE_NB_LARGE
 #define MOE_ROUTE_NB_LARGE 2
@@ -20,17 +22,21 @@ constexpr int kRouteTok = 2;  // tokens per workgroup
 // NB: router-row chunks a wave requests at once (4 for small batches, where the kernel is a chain
 // of memory round trips; fewer for large ones, where registers per wave decide how many
 // workgroups a CU holds)
-template <typename T, int NB>
+// TOK: tokens per workgroup.  Every workgroup reads the whole router (E x d fp32) once, and with
+// many tokens that re-read, not the token rows, is most of what the CUs pull in: at 2048 tokens of
+// the 2048-wide, 8-expert router 11.1 us with four tokens per workgroup against 13.5 with two (and
+// 11.2-12.1 with eight); at 512 tokens two are the faster (128 workgroups do not fill the chip).
+template <typename T, int NB, int TOK>
 __global__ __launch_bounds__(kRouteWaves* kWave) void route_kernel(
     const T* __restrict__ x, const float* __restrict__ rw, const float* __restrict__ rb,
     int32_t* __restrict__ topk_idx, float* __restrict__ topk_gate, float* __restrict__ probs,
     int T_, int d, int E, int k) {
     typedef Store<T> S;
     constexpr int VEC = S::VEC;
-    __shared__ float s_logit[kRouteTok][kMaxExperts];
+    __shared__ float s_logit[TOK][kMaxExperts];
 
-    const int t0 = blockIdx.x * kRouteTok;
-    const int ntok = min(kRouteTok, T_ - t0);
+    const int t0 = blockIdx.x * TOK;
+    const int ntok = min(TOK, T_ - t0);
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
 
@@ -41,14 +47,14 @@ __global__ __launch_bounds__(kRouteWaves* kWave) void route_kernel(
         for (int q = 0; q < VEC; ++q) out[q] = S::get(xv, q);
     };
     for (int e = wave; e < E; e += kRouteWaves) {
-        float acc[kRouteTok];
+        float acc[TOK];
         // (the bias is requested before the row is streamed: at a single token, with a cold router,
         // a load issued only after the reduction is a second full memory round trip)
         const float b = rb ? rb[e] : 0.f;
-        router_logits<VEC, kRouteTok, NB>(load_x, rw + (size_t)e * d, d, lane, ntok, acc);
+        router_logits<VEC, TOK, NB>(load_x, rw + (size_t)e * d, d, lane, ntok, acc);
         if (lane == 0) {
 #pragma unroll
-            for (int t = 0; t < kRouteTok; ++t) s_logit[t][e] = acc[t] + b;
+            for (int t = 0; t < TOK; ++t) s_logit[t][e] = acc[t] + b;
         }
     }
     __syncthreads();
@@ -159,18 +165,21 @@ int launch_route(const moe_shape& s, const void* x, const float* rw, const float
             return launch_route_lds<float>(s, (const float*)x, rw, rb, topk_idx, topk_gate, probs, st);
         return launch_route_lds<bf16_t>(s, (const bf16_t*)x, rw, rb, topk_idx, topk_gate, probs, st);
     }
-    dim3 grid((s.n_tokens + kRouteTok - 1) / kRouteTok), block(kRouteWaves * kWave);
+    const bool small = s.n_tokens <= 256, large = s.n_tokens >= kRouteLargeFrom;
+    const int tok = large ? kRouteTokLarge : kRouteTok;
+    dim3 grid((s.n_tokens + tok - 1) / tok), block(kRouteWaves * kWave);
     auto launch = [&](auto kern, auto* xp) {
         hipLaunchKernelGGL(kern, grid, block, 0, st, xp, rw, rb, topk_idx, topk_gate, probs, s.n_tokens,
                            s.d_model, s.n_experts, s.top_k);
     };
-    const bool small = s.n_tokens <= 256;
     if (s.act_dtype == MOE_F32) {
-        if (small) launch(route_kernel<float, 4>, (const float*)x);
-        else launch(route_kernel<float, MOE_ROUTE_NB_LARGE>, (const float*)x);
+        if (small) launch(route_kernel<float, 4, kRouteTok>, (const float*)x);
+        else if (!large) launch(route_kernel<float, MOE_ROUTE_NB_LARGE, kRouteTok>, (const float*)x);
+        else launch(route_kernel<float, MOE_ROUTE_NB_LARGE, kRouteTokLarge>, (const float*)x);
     } else {
-        if (small) launch(route_kernel<bf16_t, 4>, (const bf16_t*)x);
-        else launch(route_kernel<bf16_t, MOE_ROUTE_NB_LARGE>, (const bf16_t*)x);
+        if (small) launch(route_kernel<bf16_t, 4, kRouteTok>, (const bf16_t*)x);
+        else if (!large) launch(route_kernel<bf16_t, MOE_ROUTE_NB_LARGE, kRouteTok>, (const bf16_t*)x);
+        else launch(route_kernel<bf16_t, MOE_ROUTE_NB_LARGE, kRouteTokLarge>, (const bf16_t*)x);
     }
     return launch_status();
 }
