@@ -85,7 +85,7 @@ TRAFFIC_SOURCE = {
     "phone_decode": ("phone_decode_kernels_and_hbm_traffic.txt", r"gemv_kernelIDF16bLi2E"),
 }
 MEASURED_KIB = {  # workload: (FETCH_SIZE mean, WRITE_SIZE mean), KiB per dispatch as the tool reports them
-    "phone_prefill": (287868.5, 46923.6),
+    "phone_prefill": (289396.7, 46923.4),
     "phone_decode": (45126.1, 44.0),
 }
 MEASURED_TRAFFIC_BYTES = {w: int((f * FETCH_SCALE + wr * WRITE_SCALE) * 1024) for w, (f, wr) in MEASURED_KIB.items()}
