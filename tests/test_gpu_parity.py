@@ -482,7 +482,7 @@ def test_forward_few_tokens_pair_limits(dev, oracle, k, E, T, dtype):
     # two tokens on the matrix-vector path: 64 pairs is the most it takes (2 x 33 go to the grouped
     # GEMM); odd k makes a group of two pairs span both tokens; k = 1 is one pair per token
     cfg = _cfg(name=f"ft{k}{E}", d=264, F=520, E=E, k=k, dtype=dtype, seed=1300 + k + E + T, std=0.05)
-    _forward_case(dev, oracle, cfg, T, residual=bool(T % 2))
+    _forward_case(dev, oracle, cfg, T, residual=bool(k % 2))
 
 
 @pytest.mark.parametrize("name", ["phone_wd", "phone_wd_base"])
